@@ -1,0 +1,188 @@
+"""ctypes front-end of the CPU oracle (``pv_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()``
+and the ``cpu_baseline`` leg of ``bench.py``.  It never imports the HIP
+package and the HIP package never imports it.
+
+All arrays are numpy; 16-bit float data travels as ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpv_oracle.so")
+_lib = None
+
+DTYPES = {"f16": 0, "bf16": 1}
+
+
+class PoolDesc(ctypes.Structure):
+    _fields_ = [("num_pages", ctypes.c_int32), ("page_size", ctypes.c_int32),
+                ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP).  Returns the library path."""
+    srcs = [os.path.join(_HERE, "pv_oracle.c"), os.path.join(_HERE, "pv_oracle_attend.inc")]
+    if not force and os.path.exists(_LIB_PATH) and \
+            all(os.path.getmtime(_LIB_PATH) >= os.path.getmtime(s) for s in srcs):
+        return _LIB_PATH
+    cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-Wall", "-Wextra",
+           "-o", _LIB_PATH, srcs[0], "-lm"]
+    subprocess.run(cmd, check=True, cwd=_HERE)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    dp = ctypes.POINTER(PoolDesc)
+    lib.pvo_k_index.restype = ctypes.c_int64
+    lib.pvo_k_index.argtypes = [dp] + [ctypes.c_int64] * 4
+    lib.pvo_v_index.restype = ctypes.c_int64
+    lib.pvo_v_index.argtypes = [dp] + [ctypes.c_int64] * 4
+    lib.pvo_widen16.restype = ctypes.c_double
+    lib.pvo_widen16.argtypes = [ctypes.c_uint16, ctypes.c_int32]
+    lib.pvo_kv_append.restype = ctypes.c_int
+    lib.pvo_kv_append.argtypes = [dp, u16p, u16p, i32p, ctypes.c_int32, i32p, i32p, i32p,
+                                  ctypes.c_int32, u16p, u16p]
+    lib.pvo_gather_kv.restype = ctypes.c_int
+    lib.pvo_gather_kv.argtypes = [dp, u16p, u16p, i32p, ctypes.c_int32, ctypes.c_int32,
+                                  ctypes.c_int32, f64p, f64p]
+    lib.pvo_attn.restype = ctypes.c_int
+    lib.pvo_attn.argtypes = [dp, ctypes.c_int32, u16p, u16p, u16p, i32p, ctypes.c_int32, i32p,
+                             i32p, i32p, ctypes.c_int32, ctypes.c_double, u8p, ctypes.c_int32,
+                             ctypes.c_int32, f64p, ctypes.c_int32, ctypes.c_int32, f64p, i32p]
+    _lib = lib
+    return lib
+
+
+def _desc(num_pages, page_size, num_kv_heads, head_dim, dtype) -> PoolDesc:
+    return PoolDesc(int(num_pages), int(page_size), int(num_kv_heads), int(head_dim),
+                    DTYPES[dtype])
+
+
+def _p(a: Optional[np.ndarray], ctype):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc} "
+                           "(1 bad argument, 2 page index out of range, 3 out of memory)")
+
+
+def widen(bits: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact value of 16-bit patterns as float64 (element-wise, via the C routine)."""
+    lib = _load()
+    flat = np.ascontiguousarray(bits, dtype=np.uint16).ravel()
+    out = np.empty(flat.shape, dtype=np.float64)
+    code = DTYPES[dtype]
+    for i, b in enumerate(flat):
+        out[i] = lib.pvo_widen16(int(b), code)
+    return out.reshape(np.shape(bits))
+
+
+def k_index(pool: Tuple[int, int, int, int, str], page, head, slot, d) -> int:
+    return int(_load().pvo_k_index(ctypes.byref(_desc(*pool)), page, head, slot, d))
+
+
+def v_index(pool: Tuple[int, int, int, int, str], page, head, slot, d) -> int:
+    return int(_load().pvo_v_index(ctypes.byref(_desc(*pool)), page, head, slot, d))
+
+
+def kv_append(pool, k_new, v_new, page_table, slot_offsets, q_lens, q_start, k_pages, v_pages):
+    """Scatter new rows into the pools IN PLACE (uint16 arrays)."""
+    lib = _load()
+    desc = _desc(*pool)
+    page_table = _i32(page_table)
+    assert page_table.ndim == 2
+    k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+    v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    assert k_pages.dtype == np.uint16 and k_pages.flags.c_contiguous
+    assert v_pages.dtype == np.uint16 and v_pages.flags.c_contiguous
+    so, ql, qs = _i32(slot_offsets), _i32(q_lens), _i32(q_start)
+    rc = lib.pvo_kv_append(ctypes.byref(desc), _p(k_new, ctypes.c_uint16),
+                           _p(v_new, ctypes.c_uint16), _p(page_table, ctypes.c_int32),
+                           page_table.shape[1], _p(so, ctypes.c_int32), _p(ql, ctypes.c_int32),
+                           _p(qs, ctypes.c_int32), len(ql), _p(k_pages, ctypes.c_uint16),
+                           _p(v_pages, ctypes.c_uint16))
+    _check(rc, "kv_append")
+
+
+def gather_kv(pool, k_pages, v_pages, page_row, length, head):
+    """Contiguous [length, D] float64 K and V of one request / KV head."""
+    lib = _load()
+    desc = _desc(*pool)
+    D = pool[3]
+    page_row = _i32(page_row)
+    k = np.empty((length, D), dtype=np.float64)
+    v = np.empty((length, D), dtype=np.float64)
+    rc = lib.pvo_gather_kv(ctypes.byref(desc), _p(k_pages, ctypes.c_uint16),
+                           _p(v_pages, ctypes.c_uint16), _p(page_row, ctypes.c_int32),
+                           len(page_row), int(length), int(head), _p(k, ctypes.c_double),
+                           _p(v, ctypes.c_double))
+    _check(rc, "gather_kv")
+    return k, v
+
+
+def attn(pool, num_q_heads, q, k_pages, v_pages, page_table, ctx_lens, q_lens, q_start, scale,
+         unit_mask=None, precision="f64", num_threads=0, probs_of=None):
+    """Causal paged attention of the whole batch.
+
+    Returns ``out`` ([total_q, Hq, D] float64, NaN where a unit was not
+    selected), and additionally the probability rows of ``probs_of=(req, head)``
+    when given.  ``info['threads']`` reports the OpenMP team size.
+    """
+    lib = _load()
+    desc = _desc(*pool)
+    D = pool[3]
+    page_table = _i32(page_table)
+    cl, ql, qs = _i32(ctx_lens), _i32(q_lens), _i32(q_start)
+    total_q = int(ql.sum())
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    assert q.size == total_q * num_q_heads * D
+    out = np.full((total_q, num_q_heads, D), np.nan, dtype=np.float64)
+    mask = None
+    if unit_mask is not None:
+        mask = np.ascontiguousarray(unit_mask, dtype=np.uint8).ravel()
+        assert mask.size == len(ql) * pool[2]
+    probs = None
+    pr, ph = -1, -1
+    if probs_of is not None:
+        pr, ph = probs_of
+        probs = np.zeros((int(ql[pr]), int(cl[pr] + ql[pr])), dtype=np.float64)
+    threads = ctypes.c_int32(0)
+    rc = lib.pvo_attn(ctypes.byref(desc), int(num_q_heads), _p(q, ctypes.c_uint16),
+                      _p(k_pages, ctypes.c_uint16), _p(v_pages, ctypes.c_uint16),
+                      _p(page_table, ctypes.c_int32), page_table.shape[1],
+                      _p(cl, ctypes.c_int32), _p(ql, ctypes.c_int32), _p(qs, ctypes.c_int32),
+                      len(ql), float(scale), _p(mask, ctypes.c_uint8),
+                      {"f64": 0, "f32": 1}[precision], int(num_threads),
+                      _p(out, ctypes.c_double), int(pr), int(ph), _p(probs, ctypes.c_double),
+                      ctypes.byref(threads))
+    _check(rc, "attn")
+    info = {"threads": int(threads.value)}
+    if probs_of is not None:
+        return out, probs, info
+    return out, info
