@@ -1,0 +1,309 @@
+#!/usr/bin/env python3
+"""Benchmark of the multi-token paged attention hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch, as one transformer layer would run
+it: KV append of the batch's new tokens, then multi-token paged attention (both attention
+kernels and the split-KV merge).  The per-batch plan (prefix sums, work lists) is built once on
+the CPU and reused by every step, as the paper does across layers (Section 6.4); its cost is
+reported separately.  Every step uses the next of several independent KV pools ("layers") so the
+data comes from HBM, not from a cache warmed by the previous step.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
+KERNEL_NAMES = {0: "attn_narrow_kernel", 1: "attn_wide_kernel", 2: "attn_combine_kernel",
+                3: "kv_append_kernel"}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="mha13b",
+                    help="tiny | mha13b | gqa70b | long_history | decode_heavy | micro_c<ctx>")
+    ap.add_argument("--layers", type=int, default=0, help="independent KV pools cycled through "
+                    "(0 = pick so that the pools exceed 1 GiB of KV, at most 8)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="target CPU time of the oracle sample")
+    ap.add_argument("--extra", default="", help="comma list of further workloads to time "
+                    "briefly and report under 'other_workloads'")
+    return ap.parse_args()
+
+
+def make_batch(name: str):
+    from paper_2312_05516_amd import workloads as wl
+    if name.startswith("micro_c"):
+        return wl.microbench(int(name[len("micro_c"):]))
+    return wl.CONFIGS[name]()
+
+
+class DeviceBatch:
+    """Device tensors of one workload: L pools, q, new K/V, page table, plan, workspace."""
+
+    def __init__(self, b, layers: int):
+        import torch
+        from paper_2312_05516_amd import binding as pv
+        from paper_2312_05516_amd import workloads as wl
+        self.b, self.pv, self.torch = b, pv, torch
+        dev = "cuda"
+        Hq, Hkv, D = b.num_q_heads, b.num_kv_heads, b.head_dim
+        page_elems = Hkv * b.page_size * D
+        pool_bytes = 2 * b.num_pages * page_elems * 2  # K + V
+        if layers <= 0:
+            layers = int(min(8, max(2, np.ceil((1 << 30) / max(b.kv_bytes(), 1)))))
+            free, _ = torch.cuda.mem_get_info()
+            layers = int(max(1, min(layers, (free * 0.6) // pool_bytes)))
+        self.layers = layers
+        self.kp = [wl.random_values((b.num_pages, page_elems), b.dtype, b.seed * 13 + 2 * i, 1.0, dev)
+                   for i in range(layers)]
+        self.vp = [wl.random_values((b.num_pages, page_elems), b.dtype, b.seed * 13 + 2 * i + 1, 1.0,
+                                    dev) for i in range(layers)]
+        self.q = wl.random_values((b.total_q, Hq, D), b.dtype, b.seed * 13 + 101, 1.0, dev)
+        self.kn = wl.random_values((b.total_q, Hkv, D), b.dtype, b.seed * 13 + 102, 1.0, dev)
+        self.vn = wl.random_values((b.total_q, Hkv, D), b.dtype, b.seed * 13 + 103, 1.0, dev)
+        self.out = torch.empty((b.total_q, Hq, D), dtype=self.q.dtype, device=dev)
+        self.table = torch.from_numpy(b.page_table).to(dev)
+        self.desc = pv.pool_desc(b.num_pages, Hkv, D, b.dtype)
+        t0 = time.perf_counter()
+        self.plan = pv.plan_create(self.desc, Hq, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        self.plan_ms = (time.perf_counter() - t0) * 1e3
+        pv.plan_upload(self.plan)
+        self.ws = torch.empty(max(pv.plan_workspace_bytes(self.plan), 256), dtype=torch.uint8,
+                              device=dev)
+        self.items = {k: pv.plan_num_work_items(self.plan, k) for k in (0, 1, 2)}
+        torch.cuda.synchronize()
+
+    def step(self, i: int):
+        pv, l = self.pv, i % self.layers
+        pv.kv_append_planned(self.plan, self.kn, self.vn, self.table, self.kp[l], self.vp[l])
+        pv.multi_token_paged_attn_planned(self.plan, self.q, self.kp[l], self.vp[l], self.table,
+                                          self.b.scale, self.out, self.ws)
+
+    def time_steps(self, steps: int, warmup: int) -> float:
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(warmup + i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def kernel_times(self, steps: int) -> dict:
+        """Average duration of each kernel over `steps` instrumented steps (HIP events recorded by
+        the library on the launch stream around every kernel)."""
+        pv = self.pv
+        pv.plan_enable_timing(self.plan, True)
+        acc = {k: [] for k in range(4)}
+        for i in range(steps):
+            self.step(i)
+            for k in range(4):
+                ms = pv.plan_kernel_ms(self.plan, k)
+                if ms >= 0:
+                    acc[k].append(ms)
+        pv.plan_enable_timing(self.plan, False)
+        return {k: float(np.mean(v)) for k, v in acc.items() if v}
+
+    def kernel_share(self, kind: int):
+        """Algorithmic flops and bytes of the requests whose rows run in attention kernel `kind`."""
+        pv, b = self.pv, self.b
+        reqs = set()
+        for i in range(self.items[kind]):
+            reqs.add(int(pv.plan_work_item(self.plan, kind, i)[0]))
+        idx = np.array(sorted(reqs), dtype=np.int64)
+        c = b.ctx_lens[idx].astype(np.int64)
+        n = b.q_lens[idx].astype(np.int64)
+        pairs = int((n * c + n * (n + 1) // 2).sum())
+        flops = 4 * b.head_dim * b.num_q_heads * pairs
+        kv = int(2 * (c + n).sum() * b.num_kv_heads * b.head_dim * 2)
+        qo = int(2 * n.sum() * b.num_q_heads * b.head_dim * 2)
+        pt = int(4 * np.ceil((c + n) / b.page_size).sum())
+        return flops, kv + qo + pt
+
+    def close(self):
+        self.plan.destroy()
+        del self.kp, self.vp
+
+
+def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
+    attn = {k: v for k, v in ktimes.items() if k in (0, 1)}
+    if not attn:
+        return None
+    kind = max(attn, key=attn.get)
+    flops, nbytes = db.kernel_share(kind)
+    t = attn[kind] * 1e-3
+    t_hbm = nbytes / (HBM_PEAK_GBPS * 1e9)
+    t_mfma = flops / (MFMA_PEAK_TFLOPS * 1e12)
+    if t_hbm >= t_mfma:
+        ach = nbytes / t / 1e9
+        return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
+                "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
+    ach = flops / t / 1e12
+    return {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
+            "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
+
+
+def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
+    """Time the CPU oracle (fp64, as it stands) on a bounded sample of (request, KV head) units of
+    the same workload, on the host cores of this machine."""
+    import torch
+    import oracle
+    b = db.b
+    oracle.build()
+    Hq, Hkv, D = b.num_q_heads, b.num_kv_heads, b.head_dim
+    threads = len(os.sched_getaffinity(0))
+    threads = int(os.environ.get("OMP_NUM_THREADS", threads) or threads)
+    # assumed oracle speed, for sizing the sample only: ~4 GFLOP/s per thread in fp64
+    budget_flops = target_seconds * 4e9 * threads
+    G = Hq // Hkv
+    c = b.ctx_lens.astype(np.int64)
+    n = b.q_lens.astype(np.int64)
+    unit_flops = 4 * D * G * (n * c + n * (n + 1) // 2)  # per (request, KV head)
+    rng = np.random.default_rng(b.seed + 99)
+    order = rng.permutation(b.num_reqs * Hkv)
+    mask = np.zeros((b.num_reqs, Hkv), dtype=np.uint8)
+    total = 0
+    for u in order:
+        r, h = divmod(int(u), Hkv)
+        if n[r] == 0:
+            continue
+        if total > 0 and total + unit_flops[r] > budget_flops:
+            continue
+        mask[r, h] = 1
+        total += int(unit_flops[r])
+        if total >= 0.9 * budget_flops:
+            break
+    reqs = [r for r in range(b.num_reqs) if mask[r].any()]
+    # compact host copy of the sampled requests' pages (layer 0 pools, after the append)
+    pages, remap = [], {}
+    sub_table = np.full((len(reqs), b.max_pages_per_req), -1, dtype=np.int32)
+    for i, r in enumerate(reqs):
+        for lp in range(int((b.kv_lens[r] + b.page_size - 1) // b.page_size)):
+            p = int(b.page_table[r, lp])
+            if p not in remap:
+                remap[p] = len(pages)
+                pages.append(p)
+            sub_table[i, lp] = remap[p]
+    idx = torch.tensor(pages, dtype=torch.long, device="cuda")
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    sub_k = bits(db.kp[0].index_select(0, idx)).ravel()
+    sub_v = bits(db.vp[0].index_select(0, idx)).ravel()
+    rows = np.concatenate([np.arange(b.q_start[r], b.q_start[r] + b.q_lens[r]) for r in reqs])
+    q_s = bits(db.q.index_select(0, torch.from_numpy(rows.astype(np.int64)).cuda()))
+    ql = b.q_lens[reqs]
+    qs = np.concatenate([[0], np.cumsum(ql)[:-1]]).astype(np.int32)
+    pool = (len(pages), b.page_size, Hkv, D, b.dtype)
+    t0 = time.perf_counter()
+    _, info = oracle.attn(pool, Hq, q_s, sub_k, sub_v, sub_table, b.ctx_lens[reqs], ql, qs, b.scale,
+                          unit_mask=mask[reqs], num_threads=threads)
+    dt = time.perf_counter() - t0
+    units = int(mask.sum())
+    return {"value": round(total / dt / 1e12, 6), "unit": "TFLOP/s", "cores": info["threads"],
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"{units} of {b.num_reqs * Hkv} (request, KV head) units of {b.name}, "
+                      f"{total / 1e9:.2f} GFLOP, fp64 C oracle with OpenMP, attention only"}
+
+
+def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool,
+                 cpu_seconds: float) -> dict:
+    b = make_batch(name)
+    db = DeviceBatch(b, layers)
+    ms = db.time_steps(steps, warmup)
+    ktimes = db.kernel_times(min(steps, 50))
+    roof = roofline_for(db, ktimes)
+    res = {
+        "workload": name,
+        "ms_per_step": round(ms, 5),
+        "tflops": round(b.flops() / (ms * 1e-3) / 1e12, 3),
+        "kv_gbps": round(b.kv_bytes() / (ms * 1e-3) / 1e9, 1),
+        "algorithmic_gbps": round(b.algorithmic_bytes() / (ms * 1e-3) / 1e9, 1),
+        "kernel_ms": {KERNEL_NAMES[k]: round(v, 5) for k, v in ktimes.items()},
+        "roofline": roof,
+        "plan_ms": round(db.plan_ms, 3),
+        "layers": db.layers,
+        "items": {"narrow": db.items[0], "wide": db.items[1], "combine": db.items[2]},
+        "batch": {"requests": b.num_reqs, "new_tokens": b.total_q,
+                  "kv_tokens": int(b.kv_lens.sum()), "flops": b.flops(), "kv_bytes": b.kv_bytes()},
+    }
+    if with_cpu:
+        res["cpu_baseline"] = cpu_baseline(db, cpu_seconds)
+    db.close()
+    return res
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the attention shards "
+              "by KV head or by request with no exchange; see DESIGN.md). Run with --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (run it under gpurun)", file=sys.stderr)
+        sys.exit(1)
+    main_res = run_workload(args.workload, args.steps, args.warmup, args.layers,
+                            not args.no_cpu_baseline, args.cpu_seconds)
+    b = make_batch(args.workload)
+    others = []
+    for name in [x for x in args.extra.split(",") if x]:
+        r = run_workload(name, max(10, args.steps // 4), max(3, args.warmup // 4), 0, False, 0)
+        others.append({k: r[k] for k in ("workload", "ms_per_step", "tflops", "kv_gbps",
+                                         "kernel_ms", "roofline", "items")})
+    line = {
+        "metric": "multi-token paged attn TFLOP/s + effective KV GB/s (1 MI355X, % roofline)",
+        "value": main_res["tflops"],
+        "unit": "TFLOP/s",
+        "effective_kv_GBps": main_res["kv_gbps"],
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": b.dtype,
+        "data": "synthetic",
+        "config": {"workload": args.workload, "requests": b.num_reqs, "num_q_heads": b.num_q_heads,
+                   "num_kv_heads": b.num_kv_heads, "head_dim": b.head_dim,
+                   "page_size": b.page_size, "new_tokens": b.total_q,
+                   "kv_tokens": int(b.kv_lens.sum()), "layers_cycled": main_res["layers"],
+                   "step": "kv_append + multi_token_paged_attn (plan built once, reused)"},
+        "roofline": main_res["roofline"],
+        "cpu_baseline": main_res.get("cpu_baseline"),
+        "kernel_ms": main_res["kernel_ms"],
+        "plan_ms": main_res["plan_ms"],
+        "items": main_res["items"],
+    }
+    if others:
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,214 @@
+/*
+ * pv.h - C ABI of libpv: multi-token attention over a paged KV cache, and the
+ * KV append that feeds it, for one AMD MI355X (gfx950).
+ *
+ * The operation is the generalized PagedAttention of the Pensieve paper
+ * (arXiv 2312.05516, Section 4.4 "Multi-token attention for non-contiguous
+ * cache" and Section 4.4.1 "Unifying the prefill and generation phase"):
+ * every request r of a batch brings n_r >= 0 new tokens (n_r = 1 is a
+ * generation step, n_r > 1 a new prompt), its K/V rows are first stored into
+ * the slots the page table assigns to them, and then each new token attends
+ * causally to the request's c_r cached tokens plus the new tokens up to and
+ * including itself (paper Eq. 2-3 with the causal rule of Section 4.4).
+ *
+ * Conventions
+ *   - Every "device" pointer is GPU memory owned by the caller (allocate it
+ *     with anything, e.g. PyTorch).  Every "host" pointer is ordinary CPU
+ *     memory, read during the call only.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Kernel launches are asynchronous on it unless stated otherwise.
+ *   - Errors are return codes; nothing is thrown across the ABI.  Shapes,
+ *     null pointers and unsupported combinations are checked on the host
+ *     before anything is launched.  The *contents* of device index arrays are
+ *     not checked by the launching calls; pv_plan_check_page_table() checks a
+ *     host copy.
+ *   - Supported: page_size 16; head_dim 64 or 128; dtype f16 or bf16;
+ *     num_q_heads a multiple of num_kv_heads (consecutive query heads
+ *     hq = hk*G .. hk*G+G-1 share KV head hk, G = num_q_heads/num_kv_heads).
+ *     Anything else returns PV_ERR_UNSUPPORTED / PV_ERR_INVALID_ARG.
+ *
+ * Pool layout (one pool for K and one for V, 16-bit elements, P = page_size,
+ * D = head_dim, Hkv = num_kv_heads).  Page-major, then KV head; inside one
+ * (page, head) tile of P*D elements the data is grouped in runs of 8 along the
+ * dimension the attention contracts over, which is what one MFMA lane consumes:
+ *   K(page p, head h, slot s, dim d) at element (((p*Hkv+h)*(D/8) + d/8)*P + s)*8 + d%8
+ *   V(page p, head h, slot s, dim d) at element (((p*Hkv+h)*(P/8) + s/8)*D + d)*8 + s%8
+ * A logical token position t of request r lives in page
+ * page_table[r*max_pages_per_req + t/P], slot t%P.  Slots past the end of a
+ * request's last page may hold anything (including NaN); they are never used.
+ *
+ * Packed query / output layout: [total_q, num_q_heads, D], request r owns rows
+ * q_start[r] .. q_start[r]+q_lens[r]-1 (paper Section 4.4.1: the tokens of all
+ * requests are concatenated).  New K/V rows: [total_q, num_kv_heads, D].
+ */
+#ifndef PV_H_
+#define PV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PV_OK = 0,
+    PV_ERR_INVALID_ARG = 1,  /* null pointer, negative size, inconsistent arrays */
+    PV_ERR_UNSUPPORTED = 2,  /* page size / head dim / dtype outside the supported set */
+    PV_ERR_OUT_OF_RANGE = 3, /* a length needs more pages than the table has, or a page index
+                                is outside the pool, or sizes overflow 32-bit indexing */
+    PV_ERR_WORKSPACE = 4,    /* workspace missing or too small */
+    PV_ERR_HIP = 5           /* a HIP runtime call failed (no device, launch failure, ...) */
+} pv_status;
+
+typedef enum { PV_F16 = 0, PV_BF16 = 1 } pv_dtype;
+
+typedef struct {
+    int32_t num_pages;    /* pages in the pool */
+    int32_t page_size;    /* tokens per page; must be 16 */
+    int32_t num_kv_heads; /* Hkv */
+    int32_t head_dim;     /* D: 64 or 128 */
+    int32_t dtype;        /* pv_dtype of q, k, v and out */
+} pv_pool_desc;
+
+/* Opaque: the per-batch auxiliary data built once on the CPU and reused by every layer. */
+typedef struct pv_plan pv_plan;
+
+/* Human-readable name of a status code (static storage). */
+const char *pv_status_string(pv_status s);
+
+/* Bytes of ONE pool (K or V) for this description; 0 if the description is invalid. */
+size_t pv_pool_bytes(const pv_pool_desc *pool);
+
+/* Element offsets inside a pool, as documented above (host helpers for callers that fill or
+ * inspect a pool themselves).  Return -1 on an invalid description or index. */
+int64_t pv_pool_k_offset(const pv_pool_desc *pool, int32_t page, int32_t head, int32_t slot,
+                         int32_t d);
+int64_t pv_pool_v_offset(const pv_pool_desc *pool, int32_t page, int32_t head, int32_t slot,
+                         int32_t d);
+
+/*
+ * Auxiliary arrays of a batch (paper Section 6.4: cumulative sequence lengths and the like are
+ * computed once on the CPU and shared by all layers; Section 4.4.1: "some auxiliary data
+ * structure ... keeps track of each request's region").
+ *
+ * pv_plan_create is pure host code: it validates the lengths, computes
+ * q_start = exclusive prefix sum of q_lens, and splits the work of the batch into the work
+ * items the kernels consume (longest first).  ctx_lens[r] counts the tokens already cached
+ * for request r, NOT including its q_lens[r] new ones; both are host arrays of num_reqs
+ * entries.  q_lens[r] == 0 is legal (the request produces nothing); num_reqs == 0 is legal.
+ * Every request must fit its page-table row: ceil((ctx+q)/page_size) <= max_pages_per_req,
+ * else PV_ERR_OUT_OF_RANGE.  On success *plan owns host memory (and, after the first launch
+ * or pv_plan_upload, a few KB..MB of device memory) until pv_plan_destroy.
+ */
+pv_status pv_plan_create(const pv_pool_desc *pool, int32_t num_q_heads,
+                         const int32_t *ctx_lens /* host [num_reqs] */,
+                         const int32_t *q_lens /* host [num_reqs] */, int32_t num_reqs,
+                         int32_t max_pages_per_req, pv_plan **plan);
+
+/* Frees host and device memory of the plan.  The caller must make sure no launch that uses the
+ * plan is still running.  NULL is ignored. */
+void pv_plan_destroy(pv_plan *plan);
+
+/* Copies the plan's arrays to the current HIP device (allocates device memory, synchronous).
+ * Called implicitly by the first *_planned launch; calling it earlier keeps the allocation out
+ * of the first timed launch.  Idempotent. */
+pv_status pv_plan_upload(pv_plan *plan);
+
+/* Total number of new tokens (rows of q / out / k_new / v_new). */
+int32_t pv_plan_total_q(const pv_plan *plan);
+/* Host pointer to q_start[num_reqs], valid until pv_plan_destroy. */
+const int32_t *pv_plan_q_start(const pv_plan *plan);
+/* Bytes of workspace the attention launch of this plan needs (0 if none; the pointer passed
+ * must be 256-byte aligned). */
+size_t pv_plan_workspace_bytes(const pv_plan *plan);
+
+/* Work-item introspection (for tests and reports).  kind: 0 = items of the bandwidth-oriented
+ * kernel (at most 16 query rows per item), 1 = items of the matrix-core kernel, 2 = split-KV
+ * combine items.  pv_plan_work_item fills eight int32 fields:
+ *   req, kv_head, row_begin, row_count, kv_begin, kv_end, split_index, split_count
+ * where a "row" is a (new token, query head of the group) pair, row = token*G + g. */
+int32_t pv_plan_num_work_items(const pv_plan *plan, int32_t kind);
+pv_status pv_plan_work_item(const pv_plan *plan, int32_t kind, int32_t index, int32_t out[8]);
+
+/* Host-side check of a page table against the plan (host copy of the table, row stride
+ * max_pages_per_req): every page a request needs must be in [0, num_pages); and, if
+ * check_append_unique != 0, no two new tokens may land in the same (page, slot).  Pages may be
+ * shared between requests for reading (paper Section 4.3.4, sub-requests). */
+pv_status pv_plan_check_page_table(const pv_plan *plan, const int32_t *page_table /* host */,
+                                   int32_t check_append_unique);
+
+/*
+ * KV append (paper Section 4.4.1: newly generated KV-tokens are stored in their allocated slots
+ * before attention).  For request r and new token j < q_lens[r], the row
+ * k_new[q_start[r]+j, h, :] is stored at logical position ctx_lens[r]+j of that request, for
+ * every KV head h; likewise v_new.  Pure 16-bit moves: the pool image is bit-exact and slots
+ * that are not addressed keep their contents.  Destinations must be distinct.
+ *   k_new, v_new : device [total_q, Hkv, D]
+ *   page_table   : device int32 [num_reqs, max_pages_per_req]
+ *   k_pages, v_pages : device pools (pv_pool_bytes each)
+ */
+pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_new,
+                               const int32_t *page_table, void *k_pages, void *v_pages,
+                               void *stream);
+
+/*
+ * Multi-token paged attention (paper Section 4.4, Eq. 2-3).  For request r, query head hq
+ * (KV head hk = hq / G) and new token i < q_lens[r]:
+ *   s_t = scale * <q[q_start[r]+i, hq, :], K_r[t, hk, :]>     for t = 0 .. ctx_lens[r]+i
+ *   out[q_start[r]+i, hq, :] = sum_t softmax(s)_t * V_r[t, hk, :]
+ * with K_r, V_r read through the page table.  `scale` multiplies the scores (the paper's
+ * divisor is its reciprocal; 1/sqrt(D) is customary).  Scores, softmax and the weighted sum
+ * are accumulated in fp32; out is rounded to the 16-bit dtype.  Must run after the append of
+ * the same batch on the same stream.
+ *   q, out     : device [total_q, Hq, D]
+ *   workspace  : device, >= pv_plan_workspace_bytes(plan) bytes, 256-byte aligned; may be NULL
+ *                when that is 0.  Its contents are scratch (partial results of split KV
+ *                ranges); two launches that overlap in time need different workspaces.
+ */
+pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const void *k_pages,
+                                            const void *v_pages, const int32_t *page_table,
+                                            float scale, void *out, void *workspace,
+                                            size_t workspace_bytes, void *stream);
+
+/*
+ * Per-kernel timing for reports.  After pv_plan_enable_timing(plan, 1) every planned launch also
+ * records a pair of HIP events around each kernel it launches (on the launch stream; the events
+ * belong to the plan).  pv_plan_kernel_ms waits for the end event of that kernel in the plan's most
+ * recent launch and returns its duration in milliseconds; *ms = -1 if that kernel did not run.
+ * kind: 0 = bandwidth-oriented attention kernel, 1 = matrix-core attention kernel,
+ *       2 = split-KV combine, 3 = KV append.
+ */
+pv_status pv_plan_enable_timing(pv_plan *plan, int32_t enable);
+pv_status pv_plan_kernel_ms(pv_plan *plan, int32_t kind, float *ms);
+
+/*
+ * One-shot forms with explicit arrays.  They build a temporary plan from the HOST length
+ * arrays, launch, wait for the stream, and free the plan: convenient, synchronous, and not
+ * meant for the per-layer hot loop (use a plan there).  q_start must be the exclusive prefix
+ * sum of q_lens and total_q their sum, else PV_ERR_INVALID_ARG.  slot_offsets[r] is the logical
+ * position of request r's first new token (normally ctx_lens[r]).
+ */
+pv_status pv_kv_append(const pv_pool_desc *pool, const void *k_new, const void *v_new,
+                       const int32_t *page_table /* device */, int32_t max_pages_per_req,
+                       const int32_t *slot_offsets /* host */, const int32_t *q_lens /* host */,
+                       const int32_t *q_start /* host */, int32_t num_reqs, int32_t total_q,
+                       void *k_pages, void *v_pages, void *stream);
+
+pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_heads, const void *q,
+                                    const void *k_pages, const void *v_pages,
+                                    const int32_t *page_table /* device */,
+                                    int32_t max_pages_per_req, const int32_t *ctx_lens /* host */,
+                                    const int32_t *q_lens /* host */,
+                                    const int32_t *q_start /* host */, int32_t num_reqs,
+                                    int32_t total_q, float scale, void *out, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
+/* Upper bound of the workspace the one-shot attention call can need for such a batch. */
+size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, int32_t num_reqs,
+                               int32_t total_q, int32_t max_kv_len);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PV_H_ */

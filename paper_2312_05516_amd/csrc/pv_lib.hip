@@ -1,0 +1,283 @@
+// C ABI entry points that touch the GPU: plan upload, the planned launches and the one-shot forms.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "pv_plan.h"
+
+namespace pv {
+hipError_t launch_kv_append(const pv_plan *plan, const void *k_new, const void *v_new,
+                            const int32_t *page_table, void *k_pages, void *v_pages,
+                            hipStream_t stream);
+hipError_t launch_attn_narrow(const pv_plan *plan, const void *q, const void *k_pages,
+                              const void *v_pages, const int32_t *page_table, float scale,
+                              void *out, float *ws_o, float *ws_ml, hipStream_t stream);
+hipError_t launch_attn_wide(const pv_plan *plan, const void *q, const void *k_pages,
+                            const void *v_pages, const int32_t *page_table, float scale, void *out,
+                            float *ws_o, float *ws_ml, hipStream_t stream);
+hipError_t launch_attn_combine(const pv_plan *plan, const float *ws_o, const float *ws_ml,
+                               void *out, hipStream_t stream);
+
+static std::mutex g_upload_mutex;
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static pv_status upload(pv_plan *plan)
+{
+    std::lock_guard<std::mutex> lock(g_upload_mutex);
+    if (plan->uploaded) return PV_OK;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
+    struct Part { const void *src; size_t bytes; size_t off; };
+    Part parts[7] = {
+        {plan->ctx_lens.data(), plan->ctx_lens.size() * sizeof(int32_t), 0},
+        {plan->q_lens.data(), plan->q_lens.size() * sizeof(int32_t), 0},
+        {plan->q_start.data(), plan->q_start.size() * sizeof(int32_t), 0},
+        {plan->tok_req.data(), plan->tok_req.size() * sizeof(int32_t), 0},
+        {plan->narrow.data(), plan->narrow.size() * sizeof(WorkItem), 0},
+        {plan->wide.data(), plan->wide.size() * sizeof(WorkItem), 0},
+        {plan->combine.data(), plan->combine.size() * sizeof(CombineItem), 0},
+    };
+    size_t total = 0;
+    for (Part &p : parts) {
+        p.off = total;
+        total += align_up(p.bytes, 256);
+    }
+    if (total == 0) total = 256;
+    std::vector<unsigned char> staging(total, 0);
+    for (const Part &p : parts)
+        if (p.bytes) std::memcpy(staging.data() + p.off, p.src, p.bytes);
+    void *blob = nullptr;
+    if (hipMalloc(&blob, total) != hipSuccess) return PV_ERR_HIP;
+    if (hipMemcpy(blob, staging.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(blob);
+        return PV_ERR_HIP;
+    }
+    unsigned char *b = static_cast<unsigned char *>(blob);
+    plan->d_blob = blob;
+    plan->d_ctx_lens = reinterpret_cast<int32_t *>(b + parts[0].off);
+    plan->d_q_lens = reinterpret_cast<int32_t *>(b + parts[1].off);
+    plan->d_q_start = reinterpret_cast<int32_t *>(b + parts[2].off);
+    plan->d_tok_req = reinterpret_cast<int32_t *>(b + parts[3].off);
+    plan->d_narrow = reinterpret_cast<WorkItem *>(b + parts[4].off);
+    plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
+    plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
+    plan->device = dev;
+    plan->uploaded = true;
+    return PV_OK;
+}
+
+static pv_status ensure_ready(pv_plan *plan)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (!plan->uploaded) {
+        pv_status s = upload(plan);
+        if (s != PV_OK) return s;
+    }
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
+    if (dev != plan->device) return PV_ERR_INVALID_ARG;  // plan lives on another GPU
+    return PV_OK;
+}
+
+// Brackets one kernel launch with the plan's events when timing is on.
+struct KernelTimer {
+    pv_plan *plan;
+    int kind;
+    hipStream_t stream;
+    bool on;
+    KernelTimer(pv_plan *p, int k, hipStream_t s, bool ran) : plan(p), kind(k), stream(s)
+    {
+        on = p->timing && ran;
+        if (p->timing) p->event_used[k] = on;
+        if (on) (void)hipEventRecord(static_cast<hipEvent_t>(p->events[2 * k]), s);
+    }
+    ~KernelTimer()
+    {
+        if (on) (void)hipEventRecord(static_cast<hipEvent_t>(plan->events[2 * kind + 1]), stream);
+    }
+};
+
+}  // namespace pv
+
+extern "C" {
+
+pv_status pv_plan_enable_timing(pv_plan *plan, int32_t enable)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (enable) {
+        for (void *&e : plan->events) {
+            if (e) continue;
+            hipEvent_t ev;
+            if (hipEventCreate(&ev) != hipSuccess) return PV_ERR_HIP;
+            e = ev;
+        }
+    }
+    plan->timing = enable != 0;
+    return PV_OK;
+}
+
+pv_status pv_plan_kernel_ms(pv_plan *plan, int32_t kind, float *ms)
+{
+    if (!plan || !ms || kind < 0 || kind > 3) return PV_ERR_INVALID_ARG;
+    *ms = -1.f;
+    if (!plan->events[0] || !plan->event_used[kind]) return PV_OK;
+    hipEvent_t a = static_cast<hipEvent_t>(plan->events[2 * kind]);
+    hipEvent_t b = static_cast<hipEvent_t>(plan->events[2 * kind + 1]);
+    if (hipEventSynchronize(b) != hipSuccess) return PV_ERR_HIP;
+    if (hipEventElapsedTime(ms, a, b) != hipSuccess) return PV_ERR_HIP;
+    return PV_OK;
+}
+
+pv_status pv_plan_upload(pv_plan *plan)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    return pv::upload(plan);
+}
+
+void pv_plan_destroy(pv_plan *plan)
+{
+    if (!plan) return;
+    if (plan->d_blob) (void)hipFree(plan->d_blob);
+    for (void *e : plan->events)
+        if (e) (void)hipEventDestroy(static_cast<hipEvent_t>(e));
+    delete plan;
+}
+
+pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_new,
+                               const int32_t *page_table, void *k_pages, void *v_pages,
+                               void *stream)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (plan->total_q == 0) return PV_OK;
+    if (!k_new || !v_new || !page_table || !k_pages || !v_pages) return PV_ERR_INVALID_ARG;
+    pv_status s = pv::ensure_ready(plan);
+    if (s != PV_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    {
+        pv::KernelTimer t(plan, 3, st, true);
+        e = pv::launch_kv_append(plan, k_new, v_new, page_table, k_pages, v_pages, st);
+    }
+    return e == hipSuccess ? PV_OK : PV_ERR_HIP;
+}
+
+pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const void *k_pages,
+                                            const void *v_pages, const int32_t *page_table,
+                                            float scale, void *out, void *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (plan->total_q == 0) return PV_OK;
+    if (!q || !k_pages || !v_pages || !page_table || !out) return PV_ERR_INVALID_ARG;
+    if (!(scale == scale)) return PV_ERR_INVALID_ARG;
+    float *ws_o = nullptr, *ws_ml = nullptr;
+    if (plan->workspace_bytes > 0) {
+        if (!workspace || workspace_bytes < plan->workspace_bytes ||
+            (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+            return PV_ERR_WORKSPACE;
+        ws_o = static_cast<float *>(workspace);
+        ws_ml = ws_o + (size_t)plan->partial_slots * plan->pool.head_dim;
+    }
+    pv_status s = pv::ensure_ready(plan);
+    if (s != PV_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        pv::KernelTimer t(plan, 1, st, !plan->wide.empty());
+        if (pv::launch_attn_wide(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
+                                 st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    {
+        pv::KernelTimer t(plan, 0, st, !plan->narrow.empty());
+        if (pv::launch_attn_narrow(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
+                                   st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    {
+        pv::KernelTimer t(plan, 2, st, !plan->combine.empty());
+        if (pv::launch_attn_combine(plan, ws_o, ws_ml, out, st) != hipSuccess) return PV_ERR_HIP;
+    }
+    return PV_OK;
+}
+
+static pv_status check_prefix(const int32_t *q_lens, const int32_t *q_start, int32_t num_reqs,
+                              int32_t total_q)
+{
+    if (num_reqs < 0 || total_q < 0) return PV_ERR_INVALID_ARG;
+    if (num_reqs > 0 && (!q_lens || !q_start)) return PV_ERR_INVALID_ARG;
+    int64_t at = 0;
+    for (int32_t r = 0; r < num_reqs; ++r) {
+        if (q_lens[r] < 0 || q_start[r] != at) return PV_ERR_INVALID_ARG;
+        at += q_lens[r];
+    }
+    return at == total_q ? PV_OK : PV_ERR_INVALID_ARG;
+}
+
+pv_status pv_kv_append(const pv_pool_desc *pool, const void *k_new, const void *v_new,
+                       const int32_t *page_table, int32_t max_pages_per_req,
+                       const int32_t *slot_offsets, const int32_t *q_lens, const int32_t *q_start,
+                       int32_t num_reqs, int32_t total_q, void *k_pages, void *v_pages,
+                       void *stream)
+{
+    pv_status s = check_prefix(q_lens, q_start, num_reqs, total_q);
+    if (s != PV_OK) return s;
+    if (!pool || pool->num_kv_heads <= 0) return PV_ERR_INVALID_ARG;
+    pv_plan *plan = nullptr;
+    // the append only needs positions, so any head grouping is fine: use G = 1
+    s = pv_plan_create(pool, pool->num_kv_heads, slot_offsets, q_lens, num_reqs, max_pages_per_req,
+                       &plan);
+    if (s != PV_OK) return s;
+    s = pv_kv_append_planned(plan, k_new, v_new, page_table, k_pages, v_pages, stream);
+    if (s == PV_OK && plan->total_q > 0 &&
+        hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess)
+        s = PV_ERR_HIP;
+    pv_plan_destroy(plan);
+    return s;
+}
+
+pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_heads, const void *q,
+                                    const void *k_pages, const void *v_pages,
+                                    const int32_t *page_table, int32_t max_pages_per_req,
+                                    const int32_t *ctx_lens, const int32_t *q_lens,
+                                    const int32_t *q_start, int32_t num_reqs, int32_t total_q,
+                                    float scale, void *out, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    pv_status s = check_prefix(q_lens, q_start, num_reqs, total_q);
+    if (s != PV_OK) return s;
+    pv_plan *plan = nullptr;
+    s = pv_plan_create(pool, num_q_heads, ctx_lens, q_lens, num_reqs, max_pages_per_req, &plan);
+    if (s != PV_OK) return s;
+    s = pv_multi_token_paged_attn_planned(plan, q, k_pages, v_pages, page_table, scale, out,
+                                          workspace, workspace_bytes, stream);
+    if (s == PV_OK && plan->total_q > 0 &&
+        hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess)
+        s = PV_ERR_HIP;
+    pv_plan_destroy(plan);
+    return s;
+}
+
+size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, int32_t num_reqs,
+                               int32_t total_q, int32_t max_kv_len)
+{
+    if (!pv::pool_desc_valid(pool, nullptr) || num_q_heads <= 0 || num_reqs < 0 || total_q < 0 ||
+        max_kv_len < 0)
+        return 0;
+    // Splitting only happens while a kernel has fewer items than the target and never makes a
+    // part shorter than half the target share, so each kernel ends with fewer than
+    // items + split_target parts of at most 16 resp. kWideRows rows.  Independently, a row can be
+    // in at most max_kv_len / min_split_keys + 1 parts.
+    const pv::Tuning t = pv::default_tuning();
+    const int64_t rows = (int64_t)total_q * num_q_heads +
+                         (int64_t)num_reqs * pool->num_kv_heads * pv::kNarrowRows;
+    const int64_t max_parts = (int64_t)max_kv_len / t.min_split_keys + 1;
+    const int64_t by_rows = rows * max_parts;
+    const int64_t by_items = 2 * (int64_t)t.split_target * (pv::kNarrowRows + pv::kWideRows);
+    const int64_t slots = by_rows < by_items ? by_rows : by_items;
+    return (size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float);
+}
+
+}  // extern "C"

@@ -1,0 +1,335 @@
+// Host-side auxiliary data of a batch: validation, prefix sums and the work lists.
+//
+// The paper computes the per-batch auxiliary arrays (cumulative sequence lengths, each request's
+// region of the concatenated tokens) once on the CPU and reuses them in every layer (Section 6.4;
+// Section 4.4.1).  This file is that step, extended with the decomposition of the batch into work
+// items for the two attention kernels.  It is pure host code and touches no HIP API.
+#include "pv_plan.h"
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <unordered_set>
+
+namespace pv {
+
+bool pool_desc_valid(const pv_pool_desc *p, pv_status *why)
+{
+    pv_status s = PV_OK;
+    if (!p || p->num_pages <= 0 || p->num_kv_heads <= 0 || p->page_size <= 0 || p->head_dim <= 0)
+        s = PV_ERR_INVALID_ARG;
+    else if (p->page_size != 16 || (p->head_dim != 64 && p->head_dim != 128) ||
+             (p->dtype != PV_F16 && p->dtype != PV_BF16))
+        s = PV_ERR_UNSUPPORTED;
+    if (why) *why = s;
+    return s == PV_OK;
+}
+
+static int32_t env_int(const char *name, int32_t fallback)
+{
+    const char *v = std::getenv(name);
+    if (!v || !*v) return fallback;
+    char *end = nullptr;
+    long x = std::strtol(v, &end, 10);
+    if (end == v || x <= 0 || x > (1 << 24)) return fallback;
+    return (int32_t)x;
+}
+
+Tuning default_tuning()
+{
+    Tuning t;
+    t.split_target = env_int("PV_SPLIT_TARGET", 1024);
+    t.min_split_keys = env_int("PV_MIN_SPLIT_KEYS", 256);
+    t.wide_min_rows = env_int("PV_WIDE_MIN_ROWS", 1 << 24);
+    t.xcds = env_int("PV_XCDS", 8);
+    return t;
+}
+
+static int64_t item_cost(const WorkItem &w, int rows_per_step)
+{
+    const int64_t steps = (w.row_count + rows_per_step - 1) / rows_per_step;
+    return (int64_t)(w.kv_end - w.kv_begin) * steps;
+}
+
+// Cut long items into parts of the KV range when the list is too short to fill the GPU.
+static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &combine,
+                        int64_t &slots, const Tuning &tune)
+{
+    if (items.empty() || (int64_t)items.size() >= tune.split_target) return;
+    int64_t total_keys = 0;
+    for (const WorkItem &w : items) total_keys += w.kv_end - w.kv_begin;
+    int64_t chunk = (total_keys + tune.split_target - 1) / tune.split_target;
+    chunk = std::max<int64_t>(chunk, tune.min_split_keys);
+    chunk = (chunk + kKvBlock - 1) / kKvBlock * kKvBlock;
+    std::vector<WorkItem> result;
+    result.reserve(items.size() * 2);
+    for (const WorkItem &w : items) {
+        const int64_t len = w.kv_end - w.kv_begin;
+        int64_t parts = (len + chunk - 1) / chunk;
+        if (parts <= 1 || len < 2 * (int64_t)tune.min_split_keys) {
+            result.push_back(w);
+            continue;
+        }
+        int64_t part_len = (len + parts - 1) / parts;
+        part_len = (part_len + kKvBlock - 1) / kKvBlock * kKvBlock;
+        parts = (len + part_len - 1) / part_len;
+        if (parts <= 1) {
+            result.push_back(w);
+            continue;
+        }
+        CombineItem c;
+        c.req = w.req;
+        c.kv_head = w.kv_head;
+        c.row_begin = w.row_begin;
+        c.row_count = w.row_count;
+        c.partial_base = (int32_t)slots;
+        c.split_count = (int32_t)parts;
+        c.q_row0 = w.q_row0;
+        c.reserved = 0;
+        combine.push_back(c);
+        for (int64_t s = 0; s < parts; ++s) {
+            WorkItem part = w;
+            part.kv_begin = (int32_t)(w.kv_begin + s * part_len);
+            part.kv_end = (int32_t)std::min<int64_t>(w.kv_end, w.kv_begin + (s + 1) * part_len);
+            part.split_index = (int32_t)s;
+            part.split_count = (int32_t)parts;
+            part.partial_base = (int32_t)(slots + s * w.row_count);
+            result.push_back(part);
+        }
+        slots += parts * w.row_count;
+    }
+    items.swap(result);
+}
+
+// Longest first, so that the hardware's in-order workgroup dispatch approximates
+// longest-processing-time scheduling.  Ties keep the (request, head, row) order, which puts the
+// row tiles that stream the same K/V next to each other.
+static void order_items(std::vector<WorkItem> &items, int rows_per_step)
+{
+    std::stable_sort(items.begin(), items.end(), [&](const WorkItem &a, const WorkItem &b) {
+        return item_cost(a, rows_per_step) > item_cost(b, rows_per_step);
+    });
+}
+
+pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_t *ctx_lens,
+                     const int32_t *q_lens, int32_t num_reqs, int32_t max_pages_per_req,
+                     const Tuning &tune, pv_plan **out)
+{
+    if (!out) return PV_ERR_INVALID_ARG;
+    *out = nullptr;
+    pv_status why;
+    if (!pool_desc_valid(pool, &why)) return why;
+    if (num_q_heads <= 0 || num_q_heads % pool->num_kv_heads != 0) return PV_ERR_INVALID_ARG;
+    if (num_reqs < 0 || max_pages_per_req < 0) return PV_ERR_INVALID_ARG;
+    if (num_reqs > 0 && (!ctx_lens || !q_lens)) return PV_ERR_INVALID_ARG;
+    const int32_t P = pool->page_size;
+    const int32_t G = num_q_heads / pool->num_kv_heads;
+
+    int64_t total_q = 0;
+    for (int32_t r = 0; r < num_reqs; ++r) {
+        if (ctx_lens[r] < 0 || q_lens[r] < 0) return PV_ERR_INVALID_ARG;
+        const int64_t len = (int64_t)ctx_lens[r] + q_lens[r];
+        if (len > INT32_MAX - 64) return PV_ERR_OUT_OF_RANGE;
+        if (q_lens[r] > 0 && (len + P - 1) / P > max_pages_per_req) return PV_ERR_OUT_OF_RANGE;
+        if ((int64_t)q_lens[r] * G > INT32_MAX / 2) return PV_ERR_OUT_OF_RANGE;
+        total_q += q_lens[r];
+    }
+    // rows of q/out are indexed with 64-bit arithmetic in the kernels; the row count itself and
+    // the workspace slot numbers stay 32-bit
+    if (total_q > INT32_MAX / 2) return PV_ERR_OUT_OF_RANGE;
+
+    pv_plan *plan = new (std::nothrow) pv_plan();
+    if (!plan) return PV_ERR_INVALID_ARG;
+    plan->pool = *pool;
+    plan->num_q_heads = num_q_heads;
+    plan->group = G;
+    plan->num_reqs = num_reqs;
+    plan->max_pages_per_req = max_pages_per_req;
+    plan->total_q = (int32_t)total_q;
+    plan->ctx_lens.assign(ctx_lens, ctx_lens + num_reqs);
+    plan->q_lens.assign(q_lens, q_lens + num_reqs);
+    plan->q_start.resize(num_reqs);
+    plan->tok_req.resize((size_t)total_q);
+    plan->partial_slots = 0;
+    plan->uploaded = false;
+    plan->device = -1;
+    plan->d_blob = nullptr;
+    plan->timing = false;
+    for (void *&e : plan->events) e = nullptr;
+    for (bool &u : plan->event_used) u = false;
+    int32_t at = 0;
+    for (int32_t r = 0; r < num_reqs; ++r) {
+        plan->q_start[r] = at;
+        for (int32_t j = 0; j < q_lens[r]; ++j) plan->tok_req[(size_t)at + j] = r;
+        at += q_lens[r];
+    }
+
+    for (int32_t r = 0; r < num_reqs; ++r) {
+        const int32_t n = q_lens[r], c = ctx_lens[r];
+        if (n == 0) continue;
+        const int32_t rows_total = n * G;
+        for (int32_t hk = 0; hk < pool->num_kv_heads; ++hk) {
+            WorkItem w;
+            std::memset(&w, 0, sizeof w);
+            w.req = r;
+            w.kv_head = hk;
+            w.kv_begin = 0;
+            w.split_index = 0;
+            w.split_count = 1;
+            w.partial_base = -1;
+            w.q_row0 = plan->q_start[r];
+            w.ctx = c;
+            const bool use_wide = rows_total >= tune.wide_min_rows;
+            const int32_t tile = use_wide ? kWideRows : kNarrowRows;
+            for (int32_t rb = 0; rb < rows_total; rb += tile) {
+                w.row_begin = rb;
+                w.row_count = std::min(tile, rows_total - rb);
+                const int32_t last_token = (rb + w.row_count - 1) / G;
+                w.kv_end = c + last_token + 1;  // causal limit of the tile's last row
+                (use_wide ? plan->wide : plan->narrow).push_back(w);
+            }
+        }
+    }
+    int64_t slots = 0;
+    split_items(plan->narrow, plan->combine, slots, tune);
+    split_items(plan->wide, plan->combine, slots, tune);
+    if (slots > INT32_MAX / 2) {
+        delete plan;
+        return PV_ERR_OUT_OF_RANGE;
+    }
+    order_items(plan->narrow, kNarrowRows);
+    order_items(plan->wide, 32);
+    plan->partial_slots = slots;
+    // workspace: fp32 partial outputs [slots][D], then (running max, running sum) [slots][2]
+    plan->workspace_bytes = (size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float);
+    *out = plan;
+    return PV_OK;
+}
+
+}  // namespace pv
+
+// ---------------------------------------------------------------------------------------------
+// C ABI: the host-only entry points
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+const char *pv_status_string(pv_status s)
+{
+    switch (s) {
+    case PV_OK: return "ok";
+    case PV_ERR_INVALID_ARG: return "invalid argument";
+    case PV_ERR_UNSUPPORTED: return "unsupported configuration";
+    case PV_ERR_OUT_OF_RANGE: return "length or index out of range";
+    case PV_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PV_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+size_t pv_pool_bytes(const pv_pool_desc *pool)
+{
+    if (!pv::pool_desc_valid(pool, nullptr)) return 0;
+    return (size_t)pool->num_pages * pool->num_kv_heads * pool->page_size * pool->head_dim * 2u;
+}
+
+int64_t pv_pool_k_offset(const pv_pool_desc *pool, int32_t page, int32_t head, int32_t slot,
+                         int32_t d)
+{
+    if (!pv::pool_desc_valid(pool, nullptr)) return -1;
+    if (page < 0 || page >= pool->num_pages || head < 0 || head >= pool->num_kv_heads ||
+        slot < 0 || slot >= pool->page_size || d < 0 || d >= pool->head_dim)
+        return -1;
+    const int64_t tile = (int64_t)page * pool->num_kv_heads + head;
+    const int64_t chunks = pool->head_dim / 8;
+    return ((tile * chunks + d / 8) * pool->page_size + slot) * 8 + d % 8;
+}
+
+int64_t pv_pool_v_offset(const pv_pool_desc *pool, int32_t page, int32_t head, int32_t slot,
+                         int32_t d)
+{
+    if (!pv::pool_desc_valid(pool, nullptr)) return -1;
+    if (page < 0 || page >= pool->num_pages || head < 0 || head >= pool->num_kv_heads ||
+        slot < 0 || slot >= pool->page_size || d < 0 || d >= pool->head_dim)
+        return -1;
+    const int64_t tile = (int64_t)page * pool->num_kv_heads + head;
+    const int64_t groups = pool->page_size / 8;
+    return ((tile * groups + slot / 8) * pool->head_dim + d) * 8 + slot % 8;
+}
+
+pv_status pv_plan_create(const pv_pool_desc *pool, int32_t num_q_heads, const int32_t *ctx_lens,
+                         const int32_t *q_lens, int32_t num_reqs, int32_t max_pages_per_req,
+                         pv_plan **plan)
+{
+    return pv::build_plan(pool, num_q_heads, ctx_lens, q_lens, num_reqs, max_pages_per_req,
+                          pv::default_tuning(), plan);
+}
+
+int32_t pv_plan_total_q(const pv_plan *plan) { return plan ? plan->total_q : -1; }
+
+const int32_t *pv_plan_q_start(const pv_plan *plan)
+{
+    return plan ? plan->q_start.data() : nullptr;
+}
+
+size_t pv_plan_workspace_bytes(const pv_plan *plan) { return plan ? plan->workspace_bytes : 0; }
+
+int32_t pv_plan_num_work_items(const pv_plan *plan, int32_t kind)
+{
+    if (!plan) return -1;
+    switch (kind) {
+    case 0: return (int32_t)plan->narrow.size();
+    case 1: return (int32_t)plan->wide.size();
+    case 2: return (int32_t)plan->combine.size();
+    }
+    return -1;
+}
+
+pv_status pv_plan_work_item(const pv_plan *plan, int32_t kind, int32_t index, int32_t out[8])
+{
+    if (!plan || !out || index < 0) return PV_ERR_INVALID_ARG;
+    if (kind == 0 || kind == 1) {
+        const std::vector<pv::WorkItem> &v = kind == 0 ? plan->narrow : plan->wide;
+        if ((size_t)index >= v.size()) return PV_ERR_INVALID_ARG;
+        const pv::WorkItem &w = v[index];
+        const int32_t f[8] = {w.req, w.kv_head, w.row_begin, w.row_count,
+                              w.kv_begin, w.kv_end, w.split_index, w.split_count};
+        std::memcpy(out, f, sizeof f);
+        return PV_OK;
+    }
+    if (kind == 2) {
+        if ((size_t)index >= plan->combine.size()) return PV_ERR_INVALID_ARG;
+        const pv::CombineItem &c = plan->combine[index];
+        const int32_t f[8] = {c.req, c.kv_head, c.row_begin, c.row_count, 0, 0, 0, c.split_count};
+        std::memcpy(out, f, sizeof f);
+        return PV_OK;
+    }
+    return PV_ERR_INVALID_ARG;
+}
+
+pv_status pv_plan_check_page_table(const pv_plan *plan, const int32_t *page_table,
+                                   int32_t check_append_unique)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (plan->num_reqs > 0 && !page_table) return PV_ERR_INVALID_ARG;
+    const int32_t P = plan->pool.page_size;
+    std::unordered_set<int64_t> seen;
+    for (int32_t r = 0; r < plan->num_reqs; ++r) {
+        const int32_t n = plan->q_lens[r], c = plan->ctx_lens[r];
+        if (n == 0) continue;
+        const int64_t pages = ((int64_t)c + n + P - 1) / P;
+        const int32_t *row = page_table + (int64_t)r * plan->max_pages_per_req;
+        for (int64_t lp = 0; lp < pages; ++lp)
+            if (row[lp] < 0 || row[lp] >= plan->pool.num_pages) return PV_ERR_OUT_OF_RANGE;
+        if (check_append_unique) {
+            for (int32_t j = 0; j < n; ++j) {
+                const int64_t t = (int64_t)c + j;
+                const int64_t key = (int64_t)row[t / P] * P + t % P;
+                if (!seen.insert(key).second) return PV_ERR_INVALID_ARG;
+            }
+        }
+    }
+    return PV_OK;
+}
+
+}  // extern "C"

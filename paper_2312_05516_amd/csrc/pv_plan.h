@@ -1,0 +1,91 @@
+// Internal: host-side batch plan shared by the API file and the kernel launchers.
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "pv.h"
+
+namespace pv {
+
+// One unit of kernel work.  A "row" is a (new token, query head within the GQA group) pair of one
+// (request, KV head): row = token * G + g, so the rows of one KV head that can share a K/V tile
+// are contiguous and ordered by token (which keeps the causal limit monotone in the row index).
+struct WorkItem {
+    int32_t req;
+    int32_t kv_head;
+    int32_t row_begin;    // first row of the item
+    int32_t row_count;    // rows in the item
+    int32_t kv_begin;     // first logical KV position (multiple of 32 unless 0)
+    int32_t kv_end;       // one past the last logical KV position any row of the item may see
+    int32_t split_index;  // which part of the KV range this is
+    int32_t split_count;  // 1 = writes `out` directly, >1 = writes a partial result
+    int32_t partial_base; // first workspace row slot of this item (split_count > 1), else -1
+    int32_t q_row0;       // q_start[req]
+    int32_t ctx;          // ctx_lens[req]
+    int32_t reserved;
+};
+static_assert(sizeof(WorkItem) == 48, "WorkItem is read by the kernels as 12 int32");
+
+// Merge of the partial results of one split item.
+struct CombineItem {
+    int32_t req;
+    int32_t kv_head;
+    int32_t row_begin;
+    int32_t row_count;
+    int32_t partial_base; // slot of split 0, row 0; split s, row i lives at base + s*row_count + i
+    int32_t split_count;
+    int32_t q_row0;
+    int32_t reserved;
+};
+static_assert(sizeof(CombineItem) == 32, "CombineItem is read by the kernels as 8 int32");
+
+constexpr int kNarrowRows = 16;  // rows per item of the bandwidth-oriented kernel
+constexpr int kWideRows = 128;   // rows per item of the matrix-core kernel (4 waves x 32 rows)
+constexpr int kKvBlock = 32;     // keys per inner step (two pages)
+
+struct Tuning {
+    int32_t split_target;    // aim for at least this many work items per kernel
+    int32_t min_split_keys;  // never make a KV part shorter than this
+    int32_t wide_min_rows;   // (request, KV head) units with n*G >= this use the matrix-core
+                             // kernel; smaller ones are cut into 16-row items of the narrow kernel
+    int32_t xcds;            // L2 domains the work list is interleaved over
+};
+
+}  // namespace pv
+
+struct pv_plan {
+    pv_pool_desc pool;
+    int32_t num_q_heads;
+    int32_t group;  // G
+    int32_t num_reqs;
+    int32_t max_pages_per_req;
+    int32_t total_q;
+    std::vector<int32_t> ctx_lens, q_lens, q_start;
+    std::vector<int32_t> tok_req;  // [total_q] request of every new token
+    std::vector<pv::WorkItem> narrow, wide;
+    std::vector<pv::CombineItem> combine;
+    int64_t partial_slots;  // workspace row slots
+    size_t workspace_bytes;
+
+    // device copies (filled by pv_plan_upload)
+    bool uploaded;
+    int device;
+    void *d_blob;  // one allocation holding everything below
+    int32_t *d_ctx_lens, *d_q_lens, *d_q_start, *d_tok_req;
+    pv::WorkItem *d_narrow, *d_wide;
+    pv::CombineItem *d_combine;
+
+    // optional per-kernel timing: events[2*kind], events[2*kind+1] bracket kernel `kind`
+    bool timing;
+    void *events[8];
+    bool event_used[4];
+};
+
+namespace pv {
+bool pool_desc_valid(const pv_pool_desc *p, pv_status *why);
+Tuning default_tuning();
+pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_t *ctx_lens,
+                     const int32_t *q_lens, int32_t num_reqs, int32_t max_pages_per_req,
+                     const Tuning &tune, pv_plan **out);
+}  // namespace pv

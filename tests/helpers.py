@@ -70,14 +70,19 @@ class Case:
     v_pool1: np.ndarray
 
 
-def make_case(b: wl.Batch, fill: str = "nan", value_seed=None) -> Case:
-    """Draw all values of a batch on the host and lay the pools out with numpy."""
+def make_case(b: wl.Batch, fill: str = "nan", value_seed=None, k_full=None, v_full=None,
+              q=None) -> Case:
+    """Draw all values of a batch on the host (or take the given per-request [L, Hkv, D] rows and
+    queries) and lay the pools out with numpy."""
     seed = b.seed if value_seed is None else value_seed
     Hq, Hkv, D, P = b.num_q_heads, b.num_kv_heads, b.head_dim, b.page_size
     N = b.total_q
-    q = wl.as_u16(wl.random_values((N, Hq, D), b.dtype, seed * 7 + 1, b.value_std))
-    k_full, v_full = [], []
-    for r in range(b.num_reqs):
+    if q is None:
+        q = wl.as_u16(wl.random_values((N, Hq, D), b.dtype, seed * 7 + 1, b.value_std))
+    given = k_full is not None
+    if not given:
+        k_full, v_full = [], []
+    for r in range(0 if given else b.num_reqs):
         L = int(b.kv_lens[r])
         k_full.append(wl.as_u16(wl.random_values((L, Hkv, D), b.dtype, seed * 7 + 100 + 2 * r,
                                                  b.value_std)))
@@ -140,3 +145,65 @@ def dense_causal_attention(case: Case, scale=None) -> np.ndarray:
             O = Pm @ V[:, hk]
             out[s0:s0 + n, hq] = O[c:]
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# GPU side: run a Case through the C-ABI library (imports torch / the binding lazily)
+# ---------------------------------------------------------------------------------------------
+def _torch_dtype(dtype: str):
+    import torch
+    return torch.float16 if dtype == "f16" else torch.bfloat16
+
+
+def to_dev_bits(bits: np.ndarray, dtype: str):
+    """uint16 bit patterns -> CUDA tensor of the 16-bit float type (same bits)."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    return t.view(_torch_dtype(dtype))
+
+
+def from_dev_bits(t) -> np.ndarray:
+    import torch
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def gpu_run(case: Case, scale=None, page_table=None, pools=None, do_append=True, one_shot=False,
+            k_new=None, v_new=None):
+    """append + attention through libpv.  Returns (out_bits [N,Hq,D] u16, k_pool u16, v_pool u16)."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    b = case.batch
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    kp0, vp0 = pools if pools is not None else (case.k_pool0, case.v_pool0)
+    kp, vp = to_dev_bits(kp0, b.dtype), to_dev_bits(vp0, b.dtype)
+    table_h = b.page_table if page_table is None else page_table
+    table = torch.from_numpy(np.ascontiguousarray(table_h, dtype=np.int32)).cuda()
+    q = to_dev_bits(case.q, b.dtype)
+    kn = to_dev_bits(case.k_new if k_new is None else k_new, b.dtype)
+    vn = to_dev_bits(case.v_new if v_new is None else v_new, b.dtype)
+    out = torch.full((b.total_q, b.num_q_heads, b.head_dim), float("nan"),
+                     dtype=_torch_dtype(b.dtype), device="cuda")
+    sc = b.scale if scale is None else scale
+    if one_shot:
+        if do_append:
+            pv.kv_append(desc, kn, vn, table, b.max_pages_per_req, b.ctx_lens, b.q_lens, b.q_start,
+                         kp, vp)
+        nbytes = pv.attn_workspace_bytes(desc, b.num_q_heads, b.num_reqs, b.total_q,
+                                         int(b.kv_lens.max()) if b.num_reqs else 0)
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        pv.multi_token_paged_attn(desc, b.num_q_heads, q, kp, vp, table, b.max_pages_per_req,
+                                  b.ctx_lens, b.q_lens, b.q_start, sc, out, ws)
+    else:
+        plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        assert np.array_equal(pv.plan_q_start(plan), b.q_start)
+        ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
+        if do_append:
+            pv.kv_append_planned(plan, kn, vn, table, kp, vp)
+        pv.multi_token_paged_attn_planned(plan, q, kp, vp, table, sc, out, ws)
+        torch.cuda.synchronize()
+        plan.destroy()
+    torch.cuda.synchronize()
+    return from_dev_bits(out), from_dev_bits(kp).ravel(), from_dev_bits(vp).ravel()
+
+
+TOL = {"f16": 5e-3, "bf16": 2e-2}

@@ -1,0 +1,167 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header
+declares, and its pure-host entry points (plan construction, validation, pool offsets) behave."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2312_05516_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def pv():
+    from paper_2312_05516_amd import binding
+    return binding
+
+
+def test_every_declared_symbol_is_exported(pv):
+    import ctypes
+    text = open(os.path.join(ROOT, "include", "pv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(pv_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(pv.EXPORTS), declared ^ set(pv.EXPORTS)
+    lib = ctypes.CDLL(pv.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(pv):
+    names = {pv.status_string(i) for i in range(6)}
+    assert len(names) == 6 and "ok" in names
+
+
+def test_pool_bytes_and_offsets(pv):
+    desc = pv.pool_desc(5, 3, 64, "f16")
+    assert pv.pool_bytes(desc) == 5 * 3 * 16 * 64 * 2
+    assert pv.pool_bytes(pv.pool_desc(5, 3, 64, "f16", page_size=32)) == 0
+    ids = np.arange(5 * 3 * 16 * 64)
+    kv = ids.reshape(5, 3, 8, 16, 8)
+    vv = ids.reshape(5, 3, 2, 64, 8)
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        p, h, s, d = rng.integers(5), rng.integers(3), rng.integers(16), rng.integers(64)
+        assert pv.pool_k_offset(desc, p, h, s, d) == kv[p, h, d // 8, s, d % 8]
+        assert pv.pool_v_offset(desc, p, h, s, d) == vv[p, h, s // 8, d, s % 8]
+    assert pv.pool_k_offset(desc, 5, 0, 0, 0) == -1
+    assert pv.pool_v_offset(desc, 0, 0, 16, 0) == -1
+
+
+def _items(pv, plan, kind):
+    return [pv.plan_work_item(plan, kind, i) for i in range(pv.plan_num_work_items(plan, kind))]
+
+
+@pytest.mark.parametrize("name", ["tiny", "mha13b", "gqa70b", "decode_heavy"])
+def test_plan_covers_every_row_exactly_once(pv, name):
+    b = wl.CONFIGS[name]()
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    assert pv.plan_total_q(plan) == b.total_q
+    assert np.array_equal(pv.plan_q_start(plan), b.q_start)
+    G = b.num_q_heads // b.num_kv_heads
+    # for every (req, kv head, row): the KV parts that contain it must tile [0, causal limit)
+    cover = {}
+    for kind in (0, 1):
+        for it in _items(pv, plan, kind):
+            req, hk, rb, rc, k0, k1, si, sc = (int(x) for x in it)
+            assert 0 < rc <= (16 if kind == 0 else 128)
+            assert k0 % 32 == 0 and k0 < k1
+            last_tok = (rb + rc - 1) // G
+            assert k1 <= b.ctx_lens[req] + last_tok + 1
+            for row in range(rb, rb + rc):
+                cover.setdefault((req, hk, row), []).append((k0, k1, si, sc))
+    n_rows = 0
+    for r in range(b.num_reqs):
+        for hk in range(b.num_kv_heads):
+            for row in range(int(b.q_lens[r]) * G):
+                parts = sorted(cover[(r, hk, row)])
+                n_rows += 1
+                assert parts[0][0] == 0
+                for a, c in zip(parts, parts[1:]):
+                    assert a[1] == c[0]
+                # the union must reach at least this row's own causal limit
+                assert parts[-1][1] >= b.ctx_lens[r] + row // G + 1
+                assert [p[2] for p in parts] == list(range(len(parts)))
+                assert all(p[3] == len(parts) for p in parts)
+    assert n_rows == len(cover)
+    # split bookkeeping: workspace is exactly the partial rows
+    slots = sum(int(it[3]) * int(it[7]) for it in _items(pv, plan, 2))
+    assert pv.plan_workspace_bytes(plan) == slots * (b.head_dim + 2) * 4
+    plan.destroy()
+
+
+def test_plan_orders_items_longest_first(pv):
+    b = wl.decode_heavy()
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    lens = [int(it[5] - it[4]) for it in _items(pv, plan, 0)]
+    assert lens == sorted(lens, reverse=True)
+    assert len(lens) == 256 * 40
+    plan.destroy()
+
+
+def test_plan_splits_long_single_request(pv):
+    desc = pv.pool_desc(4096, 8, 128, "bf16")
+    plan = pv.plan_create(desc, 64, [50000], [1], 4096)
+    items = _items(pv, plan, 0)
+    assert len(items) > 8 and all(int(it[7]) > 1 for it in items)
+    assert pv.plan_num_work_items(plan, 2) == 8
+    assert pv.plan_workspace_bytes(plan) > 0
+    plan.destroy()
+
+
+def test_plan_rejects_bad_arguments(pv):
+    good = pv.pool_desc(64, 4, 64, "f16")
+    with pytest.raises(pv.PvError) as e:
+        pv.plan_create(pv.pool_desc(64, 4, 96, "f16"), 4, [1], [1], 4)
+    assert e.value.status == 2
+    with pytest.raises(pv.PvError) as e:
+        pv.plan_create(pv.pool_desc(64, 4, 64, "f16", page_size=32), 4, [1], [1], 4)
+    assert e.value.status == 2
+    with pytest.raises(pv.PvError) as e:
+        pv.plan_create(good, 6, [1], [1], 4)  # 6 query heads over 4 KV heads
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:
+        pv.plan_create(good, 4, [-1], [1], 4)
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:
+        pv.plan_create(good, 4, [60], [5], 4)  # 65 tokens need 5 pages, the table has 4
+    assert e.value.status == 3
+    # empty batches and empty requests are fine
+    p = pv.plan_create(good, 4, [], [], 4)
+    assert pv.plan_total_q(p) == 0 and pv.plan_num_work_items(p, 0) == 0
+    p.destroy()
+    p = pv.plan_create(good, 4, [10, 3], [0, 2], 4)
+    assert pv.plan_total_q(p) == 2 and pv.plan_q_start(p).tolist() == [0, 0]
+    p.destroy()
+
+
+def test_page_table_check(pv):
+    b = wl.custom([20, 5], [3, 4], num_q_heads=4, num_kv_heads=2, head_dim=64, seed=3)
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    plan = pv.plan_create(desc, 4, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    assert pv.plan_check_page_table(plan, b.page_table) == 0
+    bad = b.page_table.copy()
+    bad[0, 1] = b.num_pages
+    assert pv.plan_check_page_table(plan, bad) == 3
+    bad = b.page_table.copy()
+    bad[1, 0] = -1
+    assert pv.plan_check_page_table(plan, bad) == 3
+    shared = b.page_table.copy()
+    shared[1, 0] = shared[0, 1]  # request 1 would append into request 0's second page
+    assert pv.plan_check_page_table(plan, shared, check_append_unique=False) == 0
+    assert pv.plan_check_page_table(plan, shared, check_append_unique=True) == 1
+    plan.destroy()
+
+
+def test_workspace_bound_covers_plans(pv):
+    for name in ["tiny", "mha13b", "gqa70b", "decode_heavy"]:
+        b = wl.CONFIGS[name]()
+        desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+        plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        bound = pv.attn_workspace_bytes(desc, b.num_q_heads, b.num_reqs, b.total_q,
+                                        int(b.kv_lens.max()))
+        assert bound >= pv.plan_workspace_bytes(plan)
+        plan.destroy()
