@@ -41,7 +41,7 @@ Tuning default_tuning()
     Tuning t;
     t.split_target = env_int("PV_SPLIT_TARGET", 1024);
     t.min_split_keys = env_int("PV_MIN_SPLIT_KEYS", 256);
-    t.wide_min_rows = env_int("PV_WIDE_MIN_ROWS", 1 << 24);
+    t.wide_min_rows = env_int("PV_WIDE_MIN_ROWS", 33);
     t.xcds = env_int("PV_XCDS", 8);
     return t;
 }
