@@ -7,38 +7,46 @@
 // never materialised.
 //
 // Mapping to gfx950.  One workgroup = 4 wavefronts = one item; wavefront w owns rows 32w..32w+31.
-// The K/V page tiles of a 32-key block (two pages) are copied from HBM into LDS once per workgroup
-// (16 bytes per lane, fully coalesced: a (page, head) tile is contiguous in the pool) and every
-// wavefront reads its matrix-core operands from there, so the tile is shared by all 128 rows.  The
-// pool keeps runs of 8 elements along the contracted dimension together, so a plain linear copy
-// already puts the operands where 16 consecutive lanes read 256 consecutive bytes (no bank
-// conflicts, no padding, no transposes).  Scores are produced transposed, S^T = K Q^T
-// (v_mfma_f32_32x32x16), so each lane owns one query row (softmax without cross-lane traffic except
-// one exchange for the maximum) and the probabilities are already the B operand of
-// O^T += V^T P^T.  The next block's global loads are in flight while the current one is computed;
-// LDS is double-buffered with one barrier per block.
+// The K/V page tiles of a 32-key block (two pages) are copied from HBM straight into LDS
+// (global_load_lds, 16 bytes per lane, fully coalesced because a (page, head) tile is contiguous
+// in the pool; no register staging, no ds_write) into a ring of three stages, two blocks ahead of
+// their use, and every wavefront reads its matrix-core operands from there, so a tile is fetched
+// once for all 128 rows.  The pool keeps runs of 8 elements along the contracted dimension
+// together, so the plain linear copy already puts the operands where 16 consecutive lanes read 256
+// consecutive bytes (no bank conflicts, no padding, no transposes).  Scores are produced
+// transposed, S^T = K Q^T (v_mfma_f32_32x32x16), so each lane owns one query row (softmax without
+// cross-lane traffic except one exchange for the maximum) and the probabilities are already the B
+// operand of O^T += V^T P^T.  163 VGPRs and 48 KiB of LDS let three workgroups share a CU, whose
+// wavefronts overlap each other's matrix-core, vector-ALU and LDS phases.  One raw s_barrier per
+// block, preceded by a wait that leaves only the newest loads in flight.  Blocks that touch the
+// causal boundary or the end of the sequence take a separate, masked instantiation so the
+// steady-state loop has no branches.  The running maximum is only moved when a new score exceeds
+// it by more than 2^8 (softmax is shift-invariant), which makes rescaling the accumulator rare.
+#include <type_traits>
+
 #include "pv_device.h"
 
 namespace pv {
 
 template <typename T, int D>
-__global__ __launch_bounds__(256, 2) void attn_wide_kernel(
+__global__ __launch_bounds__(256, 3) void attn_wide_kernel(
     const WorkItem *__restrict__ items, const uint16_t *__restrict__ q,
     const uint16_t *__restrict__ k_pages, const uint16_t *__restrict__ v_pages,
     const int32_t *__restrict__ page_table, int32_t max_pages, int32_t num_q_heads,
-    int32_t num_kv_heads, int32_t group, float scale_log2e, uint16_t *__restrict__ out,
-    float *__restrict__ ws_o, float *__restrict__ ws_ml)
+    int32_t num_kv_heads, int32_t group, float scale_log2e, uint32_t q_sign,
+    uint16_t *__restrict__ out, float *__restrict__ ws_o, float *__restrict__ ws_ml)
 {
-    constexpr int KS = D / 16;                // k-steps of S^T = K Q^T
-    constexpr int NB = D / 32;                // 32-wide blocks of d in O^T
-    constexpr int TILE_BYTES = 16 * D * 2;    // one (page, head) tile
+    constexpr int BK = 32;                      // keys per block
+    constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T
+    constexpr int NB = D / 32;                  // 32-wide blocks of d in O^T
+    constexpr int TILE_BYTES = 16 * D * 2;      // one (page, head) tile
     constexpr int HALF_BYTES = 2 * TILE_BYTES;  // K (or V) part of a stage: two pages
-    constexpr int PASSES = HALF_BYTES / 4096;   // 16-byte loads per thread for K (same for V)
+    constexpr int PASSES = HALF_BYTES / 4096;   // 16-byte copies per lane for K (same for V)
+    constexpr int STAGES = 3;
     typedef typename T::vec8 vec8;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2][2 * HALF_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[STAGES][2 * HALF_BYTES];
 
     const WorkItem it = items[blockIdx.x];
-    const int tid = (int)threadIdx.x;
     const int lane = lane_id();
     const int w = wave_id();
     const int q32 = lane & 31;
@@ -49,10 +57,11 @@ __global__ __launch_bounds__(256, 2) void attn_wide_kernel(
     const int tok = valid ? row / group : 0;
     const int hq = it.kv_head * group + (valid ? row % group : 0);
     const int vis_end = valid ? it.ctx + tok + 1 : it.kv_end;
-    // wavefront-uniform limits: below unmasked_end nothing is masked for this wavefront's rows;
-    // at or beyond wave_end nothing is visible to them
+    // wavefront-uniform limits: below unmasked_end nothing is masked for this wavefront's rows
+    // (and no slot is past the end); at or beyond wave_end nothing is visible to them
     const int wave_rows = it.row_count - 32 * w;  // may be <= 0
-    const int unmasked_end = it.ctx + (it.row_begin + 32 * w) / group + 1;
+    int unmasked_end = it.ctx + (it.row_begin + 32 * w) / group + 1;
+    if (unmasked_end > it.kv_end) unmasked_end = it.kv_end;
     int wave_end = 0;
     if (wave_rows > 0) {
         const int last = it.row_begin + 32 * w + (wave_rows < 32 ? wave_rows : 32) - 1;
@@ -67,41 +76,38 @@ __global__ __launch_bounds__(256, 2) void attn_wide_kernel(
         for (int ks = 0; ks < KS; ++ks) {
             u32x4 raw = {0u, 0u, 0u, 0u};
             if (valid) raw = load16(qrow + 16 * ks + 8 * h);
+            raw ^= q_sign;  // a negative scale is applied as |scale| on negated queries
             qf[ks] = as_vec8<T>(raw);
         }
     }
 
-    // LDS byte offsets of this lane's operands inside a stage
-    const int key = (q32 & 0x13) | ((q32 & 4) << 1) | ((q32 & 8) >> 1);  // bits 2 and 3 swapped
+    // LDS byte offsets of this lane's operands inside a stage.  S^T row i of the K operand is fed
+    // with key pi(i) (bits 2 and 3 of i swapped) so that the accumulator registers of S^T, taken in
+    // order, are exactly the 8 consecutive keys the P^T operand of the second product needs.
+    const int key = (q32 & 0x13) | ((q32 & 4) << 1) | ((q32 & 8) >> 1);
     const int k_lds = (key >> 4) * TILE_BYTES + (h * 16 + (key & 15)) * 16;  // + ks * 512
     const int v_lds = HALF_BYTES + (h * D + q32) * 16;  // + page * TILE_BYTES + blk * 512
 
     const int32_t *pt = page_table + (int64_t)it.req * max_pages;
     const int last_pg = (it.kv_end - 1) >> 4;
     const int pg0 = it.kv_begin >> 4;
-    const int nblocks = (it.kv_end - it.kv_begin + 31) >> 5;
+    const int nblocks = (it.kv_end - it.kv_begin + BK - 1) / BK;
     const int64_t head_off = (int64_t)it.kv_head * (16 * D);
     const int64_t page_stride = (int64_t)num_kv_heads * (16 * D);
 
-    u32x4 stage_k[PASSES], stage_v[PASSES];
-    auto global_load = [&](int b) {
+    // asynchronous copy of block b into stage b % 3: wavefront w moves bytes [w*1024, w*1024+1024)
+    // of every 4 KiB pass, lane l the 16 bytes at 16*l of those
+    auto dma_block = [&](int b) {
+        unsigned char *stage = smem[b % STAGES];
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-            const int off = p * 4096 + tid * 16;       // byte offset inside the K (or V) half
-            const int pg_in = off / TILE_BYTES;         // 0 or 1
-            int pg = pg0 + 2 * b + pg_in;
-            pg = pg <= last_pg ? pg : last_pg;
-            const int64_t elem = (int64_t)pt[pg] * page_stride + head_off + (off % TILE_BYTES) / 2;
-            stage_k[p] = load16(k_pages + elem);
-            stage_v[p] = load16(v_pages + elem);
-        }
-    };
-    auto lds_store = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < PASSES; ++p) {
-            const int off = p * 4096 + tid * 16;
-            *reinterpret_cast<u32x4 *>(&smem[buf][off]) = stage_k[p];
-            *reinterpret_cast<u32x4 *>(&smem[buf][HALF_BYTES + off]) = stage_v[p];
+            const int off = p * 4096 + w * 1024;  // wavefront-uniform
+            int pg = pg0 + 2 * b + off / TILE_BYTES;
+            pg = pg <= last_pg ? pg : last_pg;  // a page past the end is never used: any valid one
+            const int64_t elem =
+                (int64_t)pt[pg] * page_stride + head_off + (off % TILE_BYTES) / 2 + lane * 8;
+            lds_dma16(k_pages + elem, stage + off);
+            lds_dma16(v_pages + elem, stage + HALF_BYTES + off);
         }
     };
 
@@ -110,12 +116,11 @@ __global__ __launch_bounds__(256, 2) void attn_wide_kernel(
     for (int blk = 0; blk < NB; ++blk)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[blk][v] = 0.f;
-    float m_run = -INFINITY;
-    float l_run = 0.f;
+    float m_run = -INFINITY;  // reference maximum of the RAW scores (before scaling)
+    float l_run = 0.f;        // this lane's share of the running sum
 
-    auto compute_block = [&](int buf, int b) {
-        const int kb0 = it.kv_begin + 32 * b;
-        const unsigned char *sb = smem[buf];
+    auto compute_block = [&](const unsigned char *sb, int kb0, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         f32x16 s;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.f;
@@ -124,48 +129,52 @@ __global__ __launch_bounds__(256, 2) void attn_wide_kernel(
             const u32x4 kf = *reinterpret_cast<const u32x4 *>(sb + k_lds + ks * 512);
             s = T::mfma32(as_vec8<T>(kf), qf[ks], s);
         }
-        float x[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) x[v] = s[v] * scale_log2e;
-        if (kb0 + 32 > unmasked_end) {
+        // register v = 8*page + j  <->  key kb0 + 16*page + 8*h + j
+        bool vis[16];
+        if constexpr (MASKED) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                // register v = 8*page + 4*a0 + b  <->  key kb0 + 16*page + 8*h + 4*a0 + b
-                const int kk = kb0 + 16 * (v >> 3) + 8 * h + (v & 7);
-                if (kk >= vis_end) x[v] = -INFINITY;
+                vis[v] = kb0 + 16 * (v >> 3) + 8 * h + (v & 7) < vis_end;
+                if (!vis[v]) s[v] = -INFINITY;
             }
         }
-        float mx = x[0];
+        float mx = s[0];
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, x[v]);
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
+        // lazy rescale: keep the old reference maximum unless the new one exceeds it by more than
+        // 2^kLazyLog2 in the scaled domain (exact, because softmax is shift-invariant; the
+        // probabilities just range up to 2^kLazyLog2 instead of 1)
+        const float m_new = (mx - m_run) * scale_log2e > kLazyLog2 ? mx : m_run;
         const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_safe);
+        const float alpha =
+            m_run == -INFINITY ? 0.f : fast_exp2((m_run - m_safe) * scale_log2e);
+        const float mc = m_safe * scale_log2e;
         m_run = m_new;
         float psum = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            x[v] = fast_exp2(x[v] - m_safe);
-            psum += x[v];
+            float p = fast_exp2(__builtin_fmaf(s[v], scale_log2e, -mc));
+            if constexpr (MASKED) p = vis[v] ? p : 0.f;
+            s[v] = p;
+            psum += p;
         }
         l_run = l_run * alpha + psum;
         if (__any(alpha != 1.f)) {
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) o[blk] *= alpha;
         }
-        const bool tail = kb0 + 32 > it.kv_end;  // slots past the end may hold anything
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg) {
             u32x4 praw;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
-                praw[jj] = T::pack2(x[8 * pg + 2 * jj], x[8 * pg + 2 * jj + 1]);
+                praw[jj] = T::pack2(s[8 * pg + 2 * jj], s[8 * pg + 2 * jj + 1]);
             const vec8 pf = as_vec8<T>(praw);
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) {
                 u32x4 vf = *reinterpret_cast<const u32x4 *>(sb + v_lds + pg * TILE_BYTES + blk * 512);
-                if (tail) {
+                if constexpr (MASKED) {  // slots past the end may hold anything: zero those values
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) {
                         const int kk = kb0 + 16 * pg + 8 * h + 2 * jj;
@@ -180,15 +189,32 @@ __global__ __launch_bounds__(256, 2) void attn_wide_kernel(
         }
     };
 
-    global_load(0);
-    lds_store(0);
-    __syncthreads();
+    // prologue: blocks 0 and 1 on their way, block 0 landed and visible to everyone
+    dma_block(0);
+    if (nblocks > 1) dma_block(1);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     for (int b = 0; b < nblocks; ++b) {
-        const bool more = b + 1 < nblocks;
-        if (more) global_load(b + 1);
-        if (it.kv_begin + 32 * b < wave_end) compute_block(b & 1, b);
-        if (more) lds_store((b + 1) & 1);
-        __syncthreads();
+        const bool more = b + 2 < nblocks;
+        if (more) dma_block(b + 2);  // its stage held block b-1, which every wavefront is done with
+        const int kb0 = it.kv_begin + BK * b;
+        if (kb0 < wave_end) {
+            if (kb0 + BK <= unmasked_end)
+                compute_block(smem[b % STAGES], kb0, std::false_type{});
+            else
+                compute_block(smem[b % STAGES], kb0, std::true_type{});
+        }
+        // block b+1 (issued one iteration ago) must have landed before the barrier publishes it;
+        // this iteration's own copies may stay in flight
+        asm volatile("" ::: "memory");
+        if (more)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PASSES));
+        else
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
     }
 
     // ---- finish: every lane owns one row; the two half-waves hold partial sums ----
@@ -218,7 +244,8 @@ __global__ __launch_bounds__(256, 2) void attn_wide_kernel(
                                                            o[blk][4 * a + 2], o[blk][4 * a + 3]};
             }
         if (h == 0) {
-            ws_ml[2 * slot] = m_run;
+            // the merge works in the log2 domain of the scaled scores
+            ws_ml[2 * slot] = m_run == -INFINITY ? -INFINITY : m_run * scale_log2e;
             ws_ml[2 * slot + 1] = l_tot;
         }
     }
@@ -230,10 +257,12 @@ static hipError_t launch_wide_t(const pv_plan *plan, const void *q, const void *
                                 void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
     const int n = (int)plan->wide.size();
+    const float c = (scale < 0.f ? -scale : scale) * kLog2e;
+    const uint32_t q_sign = scale < 0.f ? 0x80008000u : 0u;
     hipLaunchKernelGGL((attn_wide_kernel<T, D>), dim3(n), dim3(256), 0, stream, plan->d_wide,
                        (const uint16_t *)q, (const uint16_t *)k_pages, (const uint16_t *)v_pages,
                        page_table, plan->max_pages_per_req, plan->num_q_heads,
-                       plan->pool.num_kv_heads, plan->group, scale * kLog2e, (uint16_t *)out, ws_o,
+                       plan->pool.num_kv_heads, plan->group, c, q_sign, (uint16_t *)out, ws_o,
                        ws_ml);
     return hipGetLastError();
 }

@@ -17,6 +17,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazyLog2 = 8.f;  // the running maximum may lag the true one by this many powers of 2
 
 struct F16 {
     typedef f16x8 vec8;
@@ -66,6 +67,14 @@ __device__ __forceinline__ u32x4 load16(const void *p)
     return *reinterpret_cast<const u32x4 *>(p);
 }
 
+// max of x over the lane pair (l, l ^ 32), without going through LDS
+__device__ __forceinline__ float half_wave_max(float x)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // lane index of the calling thread within its wavefront, wave index made scalar
@@ -74,5 +83,27 @@ __device__ __forceinline__ int wave_id()
 {
     return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
 }
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *global_void_ptr;
+
+// Asynchronous 16-byte-per-lane copy from global memory into LDS: lane l of the wavefront writes
+// lds_base + 16*l.  Issued as raw instructions so that the compiler's wait-count insertion does
+// not serialise it against unrelated LDS reads; completion is awaited explicitly (vmcnt) before the
+// barrier that publishes the stage.  lds_base must be wavefront-uniform.  The statement rewrites
+// M0, which the compiler never keeps live across statements in these kernels (it reloads M0 next
+// to every instruction that needs it).
+__device__ __forceinline__ void lds_dma16(const void *gptr, void *lds_base)
+{
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)lds_base;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "memory");
+}
+
+// s_waitcnt immediate that waits until at most N vector-memory operations are outstanding and
+// does not wait on the other counters.
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
 }  // namespace pv

@@ -31,7 +31,7 @@ static pv_status upload(pv_plan *plan)
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
     struct Part { const void *src; size_t bytes; size_t off; };
-    Part parts[7] = {
+    Part parts[8] = {
         {plan->ctx_lens.data(), plan->ctx_lens.size() * sizeof(int32_t), 0},
         {plan->q_lens.data(), plan->q_lens.size() * sizeof(int32_t), 0},
         {plan->q_start.data(), plan->q_start.size() * sizeof(int32_t), 0},
@@ -39,6 +39,7 @@ static pv_status upload(pv_plan *plan)
         {plan->narrow.data(), plan->narrow.size() * sizeof(WorkItem), 0},
         {plan->wide.data(), plan->wide.size() * sizeof(WorkItem), 0},
         {plan->combine.data(), plan->combine.size() * sizeof(CombineItem), 0},
+        {plan->append_groups.data(), plan->append_groups.size() * sizeof(AppendGroup), 0},
     };
     size_t total = 0;
     for (Part &p : parts) {
@@ -64,6 +65,7 @@ static pv_status upload(pv_plan *plan)
     plan->d_narrow = reinterpret_cast<WorkItem *>(b + parts[4].off);
     plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
     plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
+    plan->d_append_groups = reinterpret_cast<AppendGroup *>(b + parts[7].off);
     plan->device = dev;
     plan->uploaded = true;
     return PV_OK;

@@ -165,6 +165,22 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
         at += q_lens[r];
     }
 
+    // append: runs of new tokens that share an 8-slot group of a page
+    for (int32_t r = 0; r < num_reqs; ++r) {
+        const int64_t c = ctx_lens[r], end = (int64_t)ctx_lens[r] + q_lens[r];
+        for (int64_t t = c; t < end;) {
+            const int64_t group_end = (t / 8 + 1) * 8;
+            const int64_t stop = std::min(end, group_end);
+            AppendGroup g;
+            g.req = r;
+            g.t_begin = (int32_t)t;
+            g.count = (int32_t)(stop - t);
+            g.q_row = plan->q_start[r] + (int32_t)(t - c);
+            plan->append_groups.push_back(g);
+            t = stop;
+        }
+    }
+
     for (int32_t r = 0; r < num_reqs; ++r) {
         const int32_t n = q_lens[r], c = ctx_lens[r];
         if (n == 0) continue;

@@ -40,6 +40,16 @@ struct CombineItem {
 };
 static_assert(sizeof(CombineItem) == 32, "CombineItem is read by the kernels as 8 int32");
 
+// Up to 8 consecutive new tokens of one request that fall into the same 8-slot group of a page
+// (the V pool keeps 8 consecutive slots of one head dimension in one 16-byte run).
+struct AppendGroup {
+    int32_t req;
+    int32_t t_begin;  // logical position of the first token of the group
+    int32_t count;    // 1..8 tokens
+    int32_t q_row;    // row of that first token in k_new / v_new
+};
+static_assert(sizeof(AppendGroup) == 16, "AppendGroup is read by the kernel as 4 int32");
+
 constexpr int kNarrowRows = 16;  // rows per item of the bandwidth-oriented kernel
 constexpr int kWideRows = 128;   // rows per item of the matrix-core kernel (4 waves x 32 rows)
 constexpr int kKvBlock = 32;     // keys per inner step (two pages)
@@ -65,6 +75,7 @@ struct pv_plan {
     std::vector<int32_t> tok_req;  // [total_q] request of every new token
     std::vector<pv::WorkItem> narrow, wide;
     std::vector<pv::CombineItem> combine;
+    std::vector<pv::AppendGroup> append_groups;
     int64_t partial_slots;  // workspace row slots
     size_t workspace_bytes;
 
@@ -75,6 +86,7 @@ struct pv_plan {
     int32_t *d_ctx_lens, *d_q_lens, *d_q_start, *d_tok_req;
     pv::WorkItem *d_narrow, *d_wide;
     pv::CombineItem *d_combine;
+    pv::AppendGroup *d_append_groups;
 
     // optional per-kernel timing: events[2*kind], events[2*kind+1] bracket kernel `kind`
     bool timing;
