@@ -42,6 +42,13 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle sample")
+    ap.add_argument("--serial-kernels", action="store_true",
+                    help="run every step in the library's timing mode (the two attention kernels "
+                    "one after the other instead of side by side): for rocprofv3 runs whose "
+                    "per-kernel durations should be each kernel's own")
+    ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
+                    help="also run plain device-to-device copies of this many GiB (untimed): the "
+                    "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--extra", default="", help="comma list of further workloads to time "
                     "briefly and report under 'other_workloads'")
     return ap.parse_args()
@@ -57,7 +64,7 @@ def make_batch(name: str):
 class DeviceBatch:
     """Device tensors of one workload: L pools, q, new K/V, page table, plan, workspace."""
 
-    def __init__(self, b, layers: int):
+    def __init__(self, b, layers: int, serial: bool = False):
         import torch
         from paper_2312_05516_amd import binding as pv
         from paper_2312_05516_amd import workloads as wl
@@ -85,6 +92,9 @@ class DeviceBatch:
         self.plan = pv.plan_create(self.desc, Hq, b.ctx_lens, b.q_lens, b.max_pages_per_req)
         self.plan_ms = (time.perf_counter() - t0) * 1e3
         pv.plan_upload(self.plan)
+        self.serial = serial
+        if serial:
+            pv.plan_enable_timing(self.plan, True)
         self.ws = torch.empty(max(pv.plan_workspace_bytes(self.plan), 256), dtype=torch.uint8,
                               device=dev)
         self.items = {k: pv.plan_num_work_items(self.plan, k) for k in (0, 1, 2)}
@@ -119,7 +129,7 @@ class DeviceBatch:
                 ms = pv.plan_kernel_ms(self.plan, k)
                 if ms >= 0:
                     acc[k].append(ms)
-        pv.plan_enable_timing(self.plan, False)
+        pv.plan_enable_timing(self.plan, self.serial)
         return {k: float(np.mean(v)) for k, v in acc.items() if v}
 
     def kernel_share(self, kind: int):
@@ -230,9 +240,9 @@ def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
 
 
 def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool,
-                 cpu_seconds: float) -> dict:
+                 cpu_seconds: float, serial: bool = False) -> dict:
     b = make_batch(name)
-    db = DeviceBatch(b, layers)
+    db = DeviceBatch(b, layers, serial)
     ms = db.time_steps(steps, warmup)
     ktimes = db.kernel_times(min(steps, 50))
     roof = roofline_for(db, ktimes)
@@ -267,8 +277,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (run it under gpurun)", file=sys.stderr)
         sys.exit(1)
+    if args.calibration_copy_gib > 0:
+        n = int(args.calibration_copy_gib * (1 << 30)) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     main_res = run_workload(args.workload, args.steps, args.warmup, args.layers,
-                            not args.no_cpu_baseline, args.cpu_seconds)
+                            not args.no_cpu_baseline, args.cpu_seconds, args.serial_kernels)
     b = make_batch(args.workload)
     others = []
     for name in [x for x in args.extra.split(",") if x]:

@@ -254,39 +254,47 @@ __global__ __launch_bounds__(256, 2) void attn_narrow_kernel(
 }
 
 // Merge of split-KV partial results: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// One workgroup = 8 rows of one split item (32 threads per row, D/32 output elements each).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_combine_kernel(
-    const CombineItem *__restrict__ items, const float *__restrict__ ws_o,
-    const float *__restrict__ ws_ml, int32_t num_q_heads, int32_t group,
-    uint16_t *__restrict__ out)
+    const CombineChunk *__restrict__ chunks, const CombineItem *__restrict__ items,
+    const float *__restrict__ ws_o, const float *__restrict__ ws_ml, int32_t num_q_heads,
+    int32_t group, uint16_t *__restrict__ out)
 {
-    const CombineItem it = items[blockIdx.x];
-    constexpr int PER = 4;
-    constexpr int TPR = D / PER;  // threads per row
-    const int rows_per_pass = 256 / TPR;
-    const int d0 = ((int)threadIdx.x % TPR) * PER;
-    for (int r = (int)threadIdx.x / TPR; r < it.row_count; r += rows_per_pass) {
-        float M = -INFINITY;
-        for (int s = 0; s < it.split_count; ++s) {
-            const int64_t slot = (int64_t)it.partial_base + (int64_t)s * it.row_count + r;
-            M = fmaxf(M, ws_ml[2 * slot]);
-        }
-        const float M_safe = M == -INFINITY ? 0.f : M;
-        float L = 0.f;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < it.split_count; ++s) {
-            const int64_t slot = (int64_t)it.partial_base + (int64_t)s * it.row_count + r;
-            const float wgt = fast_exp2(ws_ml[2 * slot] - M_safe);
-            L += wgt * ws_ml[2 * slot + 1];
-            acc += wgt * *reinterpret_cast<const f32x4 *>(ws_o + slot * D + d0);
-        }
-        const float inv = 1.f / L;
-        const int orow = it.row_begin + r;
-        const int otok = orow / group;
-        const int ohq = it.kv_head * group + orow % group;
-        uint16_t *dst = out + ((int64_t)(it.q_row0 + otok) * num_q_heads + ohq) * D + d0;
+    constexpr int PER = D / 32;
+    const CombineChunk ch = chunks[blockIdx.x];
+    const CombineItem it = items[ch.item];
+    const int r = ch.row0 + ((int)threadIdx.x >> 5);
+    if (r >= it.row_count) return;
+    const int d0 = ((int)threadIdx.x & 31) * PER;
+    float M = -INFINITY;
+    for (int s = 0; s < it.split_count; ++s) {
+        const int64_t slot = (int64_t)it.partial_base + (int64_t)s * it.row_count + r;
+        M = fmaxf(M, ws_ml[2 * slot]);
+    }
+    const float M_safe = M == -INFINITY ? 0.f : M;
+    float L = 0.f;
+    float acc[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) acc[e] = 0.f;
+    for (int s = 0; s < it.split_count; ++s) {
+        const int64_t slot = (int64_t)it.partial_base + (int64_t)s * it.row_count + r;
+        const float wgt = fast_exp2(ws_ml[2 * slot] - M_safe);
+        L += wgt * ws_ml[2 * slot + 1];
+        const float *po = ws_o + slot * D + d0;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) acc[e] += wgt * po[e];
+    }
+    const float inv = 1.f / L;
+    const int orow = it.row_begin + r;
+    const int otok = orow / group;
+    const int ohq = it.kv_head * group + orow % group;
+    uint16_t *dst = out + ((int64_t)(it.q_row0 + otok) * num_q_heads + ohq) * D + d0;
+    if constexpr (PER == 4) {
         *reinterpret_cast<u32x2 *>(dst) =
             u32x2{T::pack2(acc[0] * inv, acc[1] * inv), T::pack2(acc[2] * inv, acc[3] * inv)};
+    } else {
+        *reinterpret_cast<uint32_t *>(dst) = T::pack2(acc[0] * inv, acc[1] * inv);
     }
 }
 
@@ -309,10 +317,11 @@ template <typename T, int D>
 static hipError_t launch_combine_t(const pv_plan *plan, const float *ws_o, const float *ws_ml,
                                    void *out, hipStream_t stream)
 {
-    const int n = (int)plan->combine.size();
+    const int n = (int)plan->combine_chunks.size();
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3(n), dim3(256), 0, stream, plan->d_combine,
-                       ws_o, ws_ml, plan->num_q_heads, plan->group, (uint16_t *)out);
+    hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3(n), dim3(256), 0, stream,
+                       plan->d_combine_chunks, plan->d_combine, ws_o, ws_ml, plan->num_q_heads,
+                       plan->group, (uint16_t *)out);
     return hipGetLastError();
 }
 

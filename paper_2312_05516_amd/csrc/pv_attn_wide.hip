@@ -151,25 +151,27 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
             m_run == -INFINITY ? 0.f : fast_exp2((m_run - m_safe) * scale_log2e);
         const float mc = m_safe * scale_log2e;
         m_run = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            float p = fast_exp2(__builtin_fmaf(s[v], scale_log2e, -mc));
-            if constexpr (MASKED) p = vis[v] ? p : 0.f;
-            s[v] = p;
-            psum += p;
-        }
-        l_run = l_run * alpha + psum;
         if (__any(alpha != 1.f)) {
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) o[blk] *= alpha;
         }
+        // page by page: the matrix-core work of page 0 is issued before the exponentials of page 1,
+        // so that inside this wavefront the two have something to overlap with
+        float psum = 0.f;
 #pragma unroll
         for (int pg = 0; pg < 2; ++pg) {
             u32x4 praw;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                praw[jj] = T::pack2(s[8 * pg + 2 * jj], s[8 * pg + 2 * jj + 1]);
+            for (int jj = 0; jj < 4; ++jj) {
+                float p0 = fast_exp2(__builtin_fmaf(s[8 * pg + 2 * jj], scale_log2e, -mc));
+                float p1 = fast_exp2(__builtin_fmaf(s[8 * pg + 2 * jj + 1], scale_log2e, -mc));
+                if constexpr (MASKED) {
+                    p0 = vis[8 * pg + 2 * jj] ? p0 : 0.f;
+                    p1 = vis[8 * pg + 2 * jj + 1] ? p1 : 0.f;
+                }
+                psum += p0 + p1;
+                praw[jj] = T::pack2(p0, p1);
+            }
             const vec8 pf = as_vec8<T>(praw);
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) {
@@ -187,6 +189,7 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
                 o[blk] = T::mfma32(as_vec8<T>(vf), pf, o[blk]);
             }
         }
+        l_run = l_run * alpha + psum;
     };
 
     // prologue: blocks 0 and 1 on their way, block 0 landed and visible to everyone

@@ -35,7 +35,7 @@ static pv_status upload(pv_plan *plan)
         {plan->ctx_lens.data(), plan->ctx_lens.size() * sizeof(int32_t), 0},
         {plan->q_lens.data(), plan->q_lens.size() * sizeof(int32_t), 0},
         {plan->q_start.data(), plan->q_start.size() * sizeof(int32_t), 0},
-        {plan->tok_req.data(), plan->tok_req.size() * sizeof(int32_t), 0},
+        {plan->combine_chunks.data(), plan->combine_chunks.size() * sizeof(CombineChunk), 0},
         {plan->narrow.data(), plan->narrow.size() * sizeof(WorkItem), 0},
         {plan->wide.data(), plan->wide.size() * sizeof(WorkItem), 0},
         {plan->combine.data(), plan->combine.size() * sizeof(CombineItem), 0},
@@ -61,11 +61,22 @@ static pv_status upload(pv_plan *plan)
     plan->d_ctx_lens = reinterpret_cast<int32_t *>(b + parts[0].off);
     plan->d_q_lens = reinterpret_cast<int32_t *>(b + parts[1].off);
     plan->d_q_start = reinterpret_cast<int32_t *>(b + parts[2].off);
-    plan->d_tok_req = reinterpret_cast<int32_t *>(b + parts[3].off);
+    plan->d_combine_chunks = reinterpret_cast<CombineChunk *>(b + parts[3].off);
     plan->d_narrow = reinterpret_cast<WorkItem *>(b + parts[4].off);
     plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
     plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
     plan->d_append_groups = reinterpret_cast<AppendGroup *>(b + parts[7].off);
+    if (!plan->narrow.empty() && !plan->wide.empty()) {
+        hipStream_t side;
+        hipEvent_t fork, join;
+        if (hipStreamCreateWithFlags(&side, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)
+            return PV_ERR_HIP;
+        plan->side_stream = side;
+        plan->ev_fork = fork;
+        plan->ev_join = join;
+    }
     plan->device = dev;
     plan->uploaded = true;
     return PV_OK;
@@ -145,6 +156,9 @@ void pv_plan_destroy(pv_plan *plan)
     if (plan->d_blob) (void)hipFree(plan->d_blob);
     for (void *e : plan->events)
         if (e) (void)hipEventDestroy(static_cast<hipEvent_t>(e));
+    if (plan->ev_fork) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_fork));
+    if (plan->ev_join) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_join));
+    if (plan->side_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(plan->side_stream));
     delete plan;
 }
 
@@ -186,6 +200,19 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
     pv_status s = pv::ensure_ready(plan);
     if (s != PV_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // A mixed batch has work for both attention kernels; they touch disjoint rows, so the narrow
+    // one runs on the plan's side stream between a fork and a join event (not while per-kernel
+    // timing is on: then the kernels run one after the other so that each duration is its own).
+    const bool fork =
+        plan->side_stream && !plan->timing && !plan->narrow.empty() && !plan->wide.empty();
+    hipStream_t narrow_stream = st;
+    if (fork) {
+        narrow_stream = static_cast<hipStream_t>(plan->side_stream);
+        if (hipEventRecord(static_cast<hipEvent_t>(plan->ev_fork), st) != hipSuccess ||
+            hipStreamWaitEvent(narrow_stream, static_cast<hipEvent_t>(plan->ev_fork), 0) !=
+                hipSuccess)
+            return PV_ERR_HIP;
+    }
     {
         pv::KernelTimer t(plan, 1, st, !plan->wide.empty());
         if (pv::launch_attn_wide(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
@@ -193,9 +220,14 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
             return PV_ERR_HIP;
     }
     {
-        pv::KernelTimer t(plan, 0, st, !plan->narrow.empty());
+        pv::KernelTimer t(plan, 0, narrow_stream, !plan->narrow.empty());
         if (pv::launch_attn_narrow(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
-                                   st) != hipSuccess)
+                                   narrow_stream) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    if (fork) {
+        if (hipEventRecord(static_cast<hipEvent_t>(plan->ev_join), narrow_stream) != hipSuccess ||
+            hipStreamWaitEvent(st, static_cast<hipEvent_t>(plan->ev_join), 0) != hipSuccess)
             return PV_ERR_HIP;
     }
     {

@@ -150,18 +150,19 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     plan->ctx_lens.assign(ctx_lens, ctx_lens + num_reqs);
     plan->q_lens.assign(q_lens, q_lens + num_reqs);
     plan->q_start.resize(num_reqs);
-    plan->tok_req.resize((size_t)total_q);
     plan->partial_slots = 0;
     plan->uploaded = false;
     plan->device = -1;
     plan->d_blob = nullptr;
+    plan->side_stream = nullptr;
+    plan->ev_fork = nullptr;
+    plan->ev_join = nullptr;
     plan->timing = false;
     for (void *&e : plan->events) e = nullptr;
     for (bool &u : plan->event_used) u = false;
     int32_t at = 0;
     for (int32_t r = 0; r < num_reqs; ++r) {
         plan->q_start[r] = at;
-        for (int32_t j = 0; j < q_lens[r]; ++j) plan->tok_req[(size_t)at + j] = r;
         at += q_lens[r];
     }
 
@@ -217,6 +218,9 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     order_items(plan->narrow, kNarrowRows);
     order_items(plan->wide, 32);
     plan->partial_slots = slots;
+    for (size_t i = 0; i < plan->combine.size(); ++i)
+        for (int32_t r0 = 0; r0 < plan->combine[i].row_count; r0 += 8)
+            plan->combine_chunks.push_back(CombineChunk{(int32_t)i, r0});
     // workspace: fp32 partial outputs [slots][D], then (running max, running sum) [slots][2]
     plan->workspace_bytes = (size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float);
     *out = plan;

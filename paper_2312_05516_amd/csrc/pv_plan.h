@@ -40,6 +40,13 @@ struct CombineItem {
 };
 static_assert(sizeof(CombineItem) == 32, "CombineItem is read by the kernels as 8 int32");
 
+// Eight rows of one combine item: the unit of work of one merge workgroup.
+struct CombineChunk {
+    int32_t item;  // index into the combine list
+    int32_t row0;  // first row (relative to the item) of the chunk
+};
+static_assert(sizeof(CombineChunk) == 8, "CombineChunk is read by the kernel as 2 int32");
+
 // Up to 8 consecutive new tokens of one request that fall into the same 8-slot group of a page
 // (the V pool keeps 8 consecutive slots of one head dimension in one 16-byte run).
 struct AppendGroup {
@@ -72,10 +79,10 @@ struct pv_plan {
     int32_t max_pages_per_req;
     int32_t total_q;
     std::vector<int32_t> ctx_lens, q_lens, q_start;
-    std::vector<int32_t> tok_req;  // [total_q] request of every new token
     std::vector<pv::WorkItem> narrow, wide;
     std::vector<pv::CombineItem> combine;
     std::vector<pv::AppendGroup> append_groups;
+    std::vector<pv::CombineChunk> combine_chunks;
     int64_t partial_slots;  // workspace row slots
     size_t workspace_bytes;
 
@@ -83,10 +90,16 @@ struct pv_plan {
     bool uploaded;
     int device;
     void *d_blob;  // one allocation holding everything below
-    int32_t *d_ctx_lens, *d_q_lens, *d_q_start, *d_tok_req;
+    int32_t *d_ctx_lens, *d_q_lens, *d_q_start;
     pv::WorkItem *d_narrow, *d_wide;
     pv::CombineItem *d_combine;
     pv::AppendGroup *d_append_groups;
+    pv::CombineChunk *d_combine_chunks;
+
+    // second stream (default priority) and fork/join events: the two attention kernels of a mixed
+    // batch are independent and run side by side
+    void *side_stream;
+    void *ev_fork, *ev_join;
 
     // optional per-kernel timing: events[2*kind], events[2*kind+1] bracket kernel `kind`
     bool timing;
