@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle sample")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every step eagerly instead of replaying one captured HIP graph "
+                    "per KV pool (the step of a small batch is otherwise bound by host launch time)")
     ap.add_argument("--serial-kernels", action="store_true",
                     help="run every step in the library's timing mode (the two attention kernels "
                     "one after the other instead of side by side): for rocprofv3 runs whose "
@@ -64,7 +67,7 @@ def make_batch(name: str):
 class DeviceBatch:
     """Device tensors of one workload: L pools, q, new K/V, page table, plan, workspace."""
 
-    def __init__(self, b, layers: int, serial: bool = False):
+    def __init__(self, b, layers: int, serial: bool = False, use_graph: bool = True):
         import torch
         from paper_2312_05516_amd import binding as pv
         from paper_2312_05516_amd import workloads as wl
@@ -99,6 +102,21 @@ class DeviceBatch:
                               device=dev)
         self.items = {k: pv.plan_num_work_items(self.plan, k) for k in (0, 1, 2)}
         torch.cuda.synchronize()
+        self.graphs = None
+        if use_graph and not serial:
+            # one eager pass first (loads the kernels, uploads the plan), then capture the step of
+            # every pool once; the library's launches go to torch's current (capturing) stream
+            for l in range(self.layers):
+                self.step(l)
+            torch.cuda.synchronize()
+            self.graphs = []
+            cap = torch.cuda.Stream()
+            for l in range(self.layers):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=cap):
+                    self.step(l)
+                self.graphs.append(g)
+            torch.cuda.synchronize()
 
     def step(self, i: int):
         pv, l = self.pv, i % self.layers
@@ -106,14 +124,20 @@ class DeviceBatch:
         pv.multi_token_paged_attn_planned(self.plan, self.q, self.kp[l], self.vp[l], self.table,
                                           self.b.scale, self.out, self.ws)
 
+    def run_step(self, i: int):
+        if self.graphs is not None:
+            self.graphs[i % self.layers].replay()
+        else:
+            self.step(i)
+
     def time_steps(self, steps: int, warmup: int) -> float:
         torch = self.torch
         for i in range(warmup):
-            self.step(i)
+            self.run_step(i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            self.step(warmup + i)
+            self.run_step(warmup + i)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
@@ -240,9 +264,9 @@ def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
 
 
 def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool,
-                 cpu_seconds: float, serial: bool = False) -> dict:
+                 cpu_seconds: float, serial: bool = False, use_graph: bool = True) -> dict:
     b = make_batch(name)
-    db = DeviceBatch(b, layers, serial)
+    db = DeviceBatch(b, layers, serial, use_graph)
     ms = db.time_steps(steps, warmup)
     ktimes = db.kernel_times(min(steps, 50))
     roof = roofline_for(db, ktimes)
@@ -256,6 +280,7 @@ def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool
         "roofline": roof,
         "plan_ms": round(db.plan_ms, 3),
         "layers": db.layers,
+        "launch": "hipgraph" if db.graphs is not None else "eager",
         "items": {"narrow": db.items[0], "wide": db.items[1], "combine": db.items[2]},
         "batch": {"requests": b.num_reqs, "new_tokens": b.total_q,
                   "kv_tokens": int(b.kv_lens.sum()), "flops": b.flops(), "kv_bytes": b.kv_bytes()},
@@ -286,11 +311,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     main_res = run_workload(args.workload, args.steps, args.warmup, args.layers,
-                            not args.no_cpu_baseline, args.cpu_seconds, args.serial_kernels)
+                            not args.no_cpu_baseline, args.cpu_seconds, args.serial_kernels,
+                            not args.no_graph)
     b = make_batch(args.workload)
     others = []
     for name in [x for x in args.extra.split(",") if x]:
-        r = run_workload(name, max(10, args.steps // 4), max(3, args.warmup // 4), 0, False, 0)
+        r = run_workload(name, max(10, args.steps // 4), max(3, args.warmup // 4), 0, False, 0,
+                         False, not args.no_graph)
         others.append({k: r[k] for k in ("workload", "ms_per_step", "tflops", "kv_gbps",
                                          "kernel_ms", "roofline", "items")})
     line = {
@@ -311,7 +338,8 @@ def main():
                    "num_kv_heads": b.num_kv_heads, "head_dim": b.head_dim,
                    "page_size": b.page_size, "new_tokens": b.total_q,
                    "kv_tokens": int(b.kv_lens.sum()), "layers_cycled": main_res["layers"],
-                   "step": "kv_append + multi_token_paged_attn (plan built once, reused)"},
+                   "step": "kv_append + multi_token_paged_attn (plan built once, reused)",
+                   "launch": main_res["launch"]},
         "roofline": main_res["roofline"],
         "cpu_baseline": main_res.get("cpu_baseline"),
         "kernel_ms": main_res["kernel_ms"],

@@ -95,19 +95,24 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
     const int64_t head_off = (int64_t)it.kv_head * (16 * D);
     const int64_t page_stride = (int64_t)num_kv_heads * (16 * D);
 
+    const uint32_t lane_bytes = (uint32_t)lane * 16u;
+    // page ids of a block (two pages; a page past the end is never used, so any valid id will do)
+    auto page_ids = [&](int b, int &id0, int &id1) {
+        const int pg = pg0 + 2 * b;
+        id0 = pt[pg <= last_pg ? pg : last_pg];
+        id1 = pt[pg + 1 <= last_pg ? pg + 1 : last_pg];
+    };
     // asynchronous copy of block b into stage b % 3: wavefront w moves bytes [w*1024, w*1024+1024)
-    // of every 4 KiB pass, lane l the 16 bytes at 16*l of those
-    auto dma_block = [&](int b) {
+    // of every 4 KiB pass, lane l the 16 bytes at 16*l of those (scalar base + lane offset)
+    auto dma_block = [&](int b, int id0, int id1) {
         unsigned char *stage = smem[b % STAGES];
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
             const int off = p * 4096 + w * 1024;  // wavefront-uniform
-            int pg = pg0 + 2 * b + off / TILE_BYTES;
-            pg = pg <= last_pg ? pg : last_pg;  // a page past the end is never used: any valid one
-            const int64_t elem =
-                (int64_t)pt[pg] * page_stride + head_off + (off % TILE_BYTES) / 2 + lane * 8;
-            lds_dma16(k_pages + elem, stage + off);
-            lds_dma16(v_pages + elem, stage + HALF_BYTES + off);
+            const int page = off / TILE_BYTES ? id1 : id0;
+            const int64_t elem = (int64_t)page * page_stride + head_off + (off % TILE_BYTES) / 2;
+            lds_dma16(k_pages + elem, lane_bytes, stage + off);
+            lds_dma16(v_pages + elem, lane_bytes, stage + HALF_BYTES + off);
         }
     };
 
@@ -192,16 +197,24 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
         l_run = l_run * alpha + psum;
     };
 
-    // prologue: blocks 0 and 1 on their way, block 0 landed and visible to everyone
-    dma_block(0);
-    if (nblocks > 1) dma_block(1);
+    // prologue: blocks 0 and 1 on their way, block 0 landed and visible to everyone; the page ids
+    // of the block after next are always fetched one iteration early
+    int id0, id1;
+    page_ids(0, id0, id1);
+    dma_block(0, id0, id1);
+    if (nblocks > 1) {
+        page_ids(1, id0, id1);
+        dma_block(1, id0, id1);
+    }
+    page_ids(2, id0, id1);
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     for (int b = 0; b < nblocks; ++b) {
         const bool more = b + 2 < nblocks;
-        if (more) dma_block(b + 2);  // its stage held block b-1, which every wavefront is done with
+        if (more) dma_block(b + 2, id0, id1);  // its stage held block b-1: everyone is done with it
+        page_ids(b + 3, id0, id1);
         const int kb0 = it.kv_begin + BK * b;
         if (kb0 < wave_end) {
             if (kb0 + BK <= unmasked_end)

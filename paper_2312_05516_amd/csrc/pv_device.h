@@ -93,12 +93,14 @@ typedef const __attribute__((address_space(1))) void *global_void_ptr;
 // barrier that publishes the stage.  lds_base must be wavefront-uniform.  The statement rewrites
 // M0, which the compiler never keeps live across statements in these kernels (it reloads M0 next
 // to every instruction that needs it).
-__device__ __forceinline__ void lds_dma16(const void *gptr, void *lds_base)
+__device__ __forceinline__ void lds_dma16(const void *uniform_base, uint32_t lane_offset,
+                                          void *lds_base)
 {
+    // address = wavefront-uniform 64-bit base (scalar registers) + per-lane 32-bit byte offset
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_ptr)lds_base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr), "v"(gptr)
+                 : "s"(lds_addr), "v"(lane_offset), "s"(uniform_base)
                  : "memory");
 }
 

@@ -102,14 +102,63 @@ static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &
     items.swap(result);
 }
 
-// Longest first, so that the hardware's in-order workgroup dispatch approximates
-// longest-processing-time scheduling.  Ties keep the (request, head, row) order, which puts the
-// row tiles that stream the same K/V next to each other.
-static void order_items(std::vector<WorkItem> &items, int rows_per_step)
+// Order of the work list = order of workgroup dispatch.  Two goals:
+//  * longest first, so that in-order dispatch approximates longest-processing-time scheduling;
+//  * items that stream the same K/V (the row tiles of one (request, KV head, KV part)) should run
+//    at the same time on the same XCD, so that the second and later tiles hit in that XCD's L2.
+//    Workgroup i of a launch goes to XCD i % xcds, so a group's items are placed `xcds` positions
+//    apart.  Groups are dealt to the XCDs greedily by accumulated cost (longest group first).
+static void order_items(std::vector<WorkItem> &items, int rows_per_step, int xcds)
 {
-    std::stable_sort(items.begin(), items.end(), [&](const WorkItem &a, const WorkItem &b) {
-        return item_cost(a, rows_per_step) > item_cost(b, rows_per_step);
+    if (items.empty()) return;
+    if (xcds < 1) xcds = 1;
+    // 1. group by (req, kv_head, split_index); items of a group keep their row order
+    std::stable_sort(items.begin(), items.end(), [](const WorkItem &a, const WorkItem &b) {
+        if (a.req != b.req) return a.req < b.req;
+        if (a.kv_head != b.kv_head) return a.kv_head < b.kv_head;
+        return a.split_index < b.split_index;
     });
+    struct Group { size_t begin, end; int64_t cost; };
+    std::vector<Group> groups;
+    for (size_t i = 0; i < items.size();) {
+        size_t j = i;
+        int64_t cost = 0;
+        while (j < items.size() && items[j].req == items[i].req &&
+               items[j].kv_head == items[i].kv_head && items[j].split_index == items[i].split_index) {
+            cost += item_cost(items[j], rows_per_step);
+            ++j;
+        }
+        groups.push_back(Group{i, j, cost});
+        i = j;
+    }
+    // 2. longest group first (per item, so that a long single item is not hidden behind a group of
+    //    many short ones), dealt to the least loaded XCD
+    std::stable_sort(groups.begin(), groups.end(), [&](const Group &a, const Group &b) {
+        return a.cost * (int64_t)(b.end - b.begin) > b.cost * (int64_t)(a.end - a.begin);
+    });
+    std::vector<std::vector<WorkItem>> queue((size_t)xcds);
+    std::vector<int64_t> load((size_t)xcds, 0);
+    for (const Group &g : groups) {
+        size_t best = 0;
+        for (size_t x = 1; x < (size_t)xcds; ++x)
+            if (load[x] < load[best]) best = x;
+        for (size_t i = g.begin; i < g.end; ++i) queue[best].push_back(items[i]);
+        load[best] += g.cost;
+    }
+    // 3. interleave: position k*xcds + x takes the k-th item of XCD x's queue; once a queue is
+    //    empty its positions are filled from the queues that still have items
+    std::vector<WorkItem> out;
+    out.reserve(items.size());
+    std::vector<size_t> at((size_t)xcds, 0);
+    size_t x = 0;
+    while (out.size() < items.size()) {
+        size_t pick = x;
+        for (int tries = 0; tries < xcds && at[pick] >= queue[pick].size(); ++tries)
+            pick = (pick + 1) % (size_t)xcds;
+        out.push_back(queue[pick][at[pick]++]);
+        x = (x + 1) % (size_t)xcds;
+    }
+    items.swap(out);
 }
 
 pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_t *ctx_lens,
@@ -215,8 +264,8 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
         delete plan;
         return PV_ERR_OUT_OF_RANGE;
     }
-    order_items(plan->narrow, kNarrowRows);
-    order_items(plan->wide, 32);
+    order_items(plan->narrow, kNarrowRows, tune.xcds);
+    order_items(plan->wide, 32, tune.xcds);
     plan->partial_slots = slots;
     for (size_t i = 0; i < plan->combine.size(); ++i)
         for (int32_t r0 = 0; r0 < plan->combine[i].row_count; r0 += 8)

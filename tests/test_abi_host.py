@@ -92,13 +92,27 @@ def test_plan_covers_every_row_exactly_once(pv, name):
     plan.destroy()
 
 
-def test_plan_orders_items_longest_first(pv):
+def test_plan_orders_items_longest_first_per_xcd(pv):
+    """Workgroup i goes to XCD i % 8: every XCD sees its items longest first, and the tiles of one
+    (request, KV head) sit on one XCD."""
     b = wl.decode_heavy()
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
     lens = [int(it[5] - it[4]) for it in _items(pv, plan, 0)]
-    assert lens == sorted(lens, reverse=True)
     assert len(lens) == 256 * 40
+    for x in range(8):
+        q = lens[x::8]
+        assert q == sorted(q, reverse=True)
+    plan.destroy()
+    b = wl.long_history()
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    items = _items(pv, plan, 1)
+    assert len(items) == 8 * 8 * 32
+    home = {}
+    for i, it in enumerate(items):
+        home.setdefault((int(it[0]), int(it[1])), set()).add(i % 8)
+    assert all(len(v) == 1 for v in home.values())
     plan.destroy()
 
 

@@ -293,3 +293,49 @@ def test_full_size_long_history(oracle):
     order = np.argsort(b.kv_lens)
     # the oracle is O(n * L * D) per head: two requests x one KV head (8 query heads) stays ~20 s
     _full_size_parity(oracle, b, [int(order[0]), int(order[-1])], [3])
+
+
+def test_graph_replay_matches_eager(oracle):
+    """The planned calls of a mixed batch (append, both attention kernels on two streams, the
+    merge) captured into one HIP graph: every replay must reproduce the eager result bit for bit,
+    with eager work and synchronisations between the replays."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    b = wl.custom([700, 40, 2200, 5], [1, 70, 3, 150], num_q_heads=8, num_kv_heads=2, head_dim=128,
+                  dtype="bf16", seed=61)
+    case = H.make_case(b, fill="nan")
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    assert pv.plan_num_work_items(plan, 0) > 0 and pv.plan_num_work_items(plan, 1) > 0
+    assert pv.plan_num_work_items(plan, 2) > 0
+    table = torch.from_numpy(b.page_table).cuda()
+    q = H.to_dev_bits(case.q, b.dtype)
+    kn, vn = H.to_dev_bits(case.k_new, b.dtype), H.to_dev_bits(case.v_new, b.dtype)
+    kp, vp = H.to_dev_bits(case.k_pool0, b.dtype), H.to_dev_bits(case.v_pool0, b.dtype)
+    ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
+    out = torch.zeros((b.total_q, b.num_q_heads, b.head_dim), dtype=q.dtype, device="cuda")
+
+    def step():
+        pv.kv_append_planned(plan, kn, vn, table, kp, vp)
+        pv.multi_token_paged_attn_planned(plan, q, kp, vp, table, b.scale, out, ws)
+
+    step()
+    torch.cuda.synchronize()
+    eager = H.from_dev_bits(out).copy()
+    want = oracle_out(oracle, case)
+    assert np.abs(H.bits_to_f64(eager, b.dtype) - want).max() <= H.TOL[b.dtype]
+    g = torch.cuda.CUDAGraph()
+    cap = torch.cuda.Stream()
+    with torch.cuda.graph(g, stream=cap):
+        step()
+    for rep in range(4):
+        out.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(H.from_dev_bits(out), eager), rep
+        step()  # eager work between replays
+        torch.cuda.synchronize()
+        assert np.array_equal(H.from_dev_bits(out), eager), rep
+    plan.destroy()
