@@ -150,7 +150,8 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
         // lazy rescale: keep the old reference maximum unless the new one exceeds it by more than
         // 2^kLazyLog2 in the scaled domain (exact, because softmax is shift-invariant; the
         // probabilities just range up to 2^kLazyLog2 instead of 1)
-        const float m_new = (mx - m_run) * scale_log2e > kLazyLog2 ? mx : m_run;
+        const float m_new =
+            (m_run == -INFINITY || (mx - m_run) * scale_log2e > kLazyLog2) ? mx : m_run;
         const float m_safe = m_new == -INFINITY ? 0.f : m_new;
         const float alpha =
             m_run == -INFINITY ? 0.f : fast_exp2((m_run - m_safe) * scale_log2e);

@@ -339,3 +339,25 @@ def test_graph_replay_matches_eager(oracle):
         torch.cuda.synchronize()
         assert np.array_equal(H.from_dev_bits(out), eager), rep
     plan.destroy()
+
+
+@pytest.mark.parametrize("scale", [-0.25, 0.0, 3.0])
+def test_unusual_scales(oracle, scale):
+    """`scale` is any finite multiplier: negative (the kernels negate the queries), zero (uniform
+    weights over the visible positions) and large (near one-hot)."""
+    b = wl.custom([70, 300, 9], [1, 45, 140], num_q_heads=4, num_kv_heads=2, head_dim=64,
+                  dtype="f16", seed=67, value_std=0.5)
+    case = H.make_case(b, fill="nan")
+    got_bits, _, _ = H.gpu_run(case, scale=scale)
+    got = H.bits_to_f64(got_bits, b.dtype)
+    want = oracle_out(oracle, case, scale=scale)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= H.TOL[b.dtype]
+
+
+def test_long_prefill_from_empty_cache(oracle):
+    """A 1500-token prompt with nothing cached (12 row tiles, causal diagonal in every one) next to
+    requests that bring nothing."""
+    b = wl.custom([0, 33, 0], [1500, 0, 1], num_q_heads=2, num_kv_heads=1, head_dim=128,
+                  dtype="bf16", seed=71)
+    check_case(oracle, H.make_case(b, fill="nan"))
