@@ -45,7 +45,13 @@ def _load():
     if _lib is not None:
         return _lib
     build()
-    lib = ctypes.CDLL(_LIB_PATH)
+    _lib = _bind(ctypes.CDLL(_LIB_PATH))
+    return _lib
+
+
+def _bind(lib):
+    """Declare the argument types of an oracle library (also used by the tests that load
+    deliberately broken builds of it)."""
     i32p = ctypes.POINTER(ctypes.c_int32)
     u16p = ctypes.POINTER(ctypes.c_uint16)
     f64p = ctypes.POINTER(ctypes.c_double)
@@ -67,7 +73,6 @@ def _load():
     lib.pvo_attn.argtypes = [dp, ctypes.c_int32, u16p, u16p, u16p, i32p, ctypes.c_int32, i32p,
                              i32p, i32p, ctypes.c_int32, ctypes.c_double, u8p, ctypes.c_int32,
                              ctypes.c_int32, f64p, ctypes.c_int32, ctypes.c_int32, f64p, i32p]
-    _lib = lib
     return lib
 
 
