@@ -95,11 +95,11 @@ __global__ __launch_bounds__(256, 2) void attn_narrow_kernel(
         for (int t = 0; t < 2; ++t) {
             const uint16_t *kb = k_pages + (ksel[t] ? base1 : base0) + koff[t];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) f.k[t][ks] = load16(kb + ks * (4 * 16 * 8));
+            for (int ks = 0; ks < KS; ++ks) f.k[t][ks] = load16_stream(kb + ks * (4 * 16 * 8));
         }
         const uint16_t *vb = v_pages + (vsel ? base1 : base0) + voff;
 #pragma unroll
-        for (int blk = 0; blk < NB; ++blk) f.v[blk] = load16(vb + blk * (16 * 8));
+        for (int blk = 0; blk < NB; ++blk) f.v[blk] = load16_stream(vb + blk * (16 * 8));
     };
 
     f32x4 o[NB];

@@ -75,6 +75,12 @@ __device__ __forceinline__ float half_wave_max(float x)
     return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
 }
 
+// 16-byte load with the streaming (non-temporal) hint: for data that is read once
+__device__ __forceinline__ u32x4 load16_stream(const void *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // lane index of the calling thread within its wavefront, wave index made scalar

@@ -1,6 +1,7 @@
 // C ABI entry points that touch the GPU: plan upload, the planned launches and the one-shot forms.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -66,7 +67,7 @@ static pv_status upload(pv_plan *plan)
     plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
     plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
     plan->d_append_groups = reinterpret_cast<AppendGroup *>(b + parts[7].off);
-    if (!plan->narrow.empty() && !plan->wide.empty()) {
+    if (!plan->narrow.empty() && !plan->wide.empty() && !std::getenv("PV_NO_SIDE_STREAM")) {
         hipStream_t side;
         hipEvent_t fork, join;
         if (hipStreamCreateWithFlags(&side, hipStreamNonBlocking) != hipSuccess ||
