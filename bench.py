@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the oracle sample")
+    ap.add_argument("--microbench", action="store_true",
+                    help="instead of the step benchmark, time the attention call on the shape of the "
+                    "paper's kernel figure (32 requests x 8 query tokens, context sweep) against our "
+                    "own contiguous, copy-out and one-token-per-round variants")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying one captured HIP graph "
                     "per KV pool (the step of a small batch is otherwise bound by host launch time)")
@@ -52,8 +56,9 @@ def parse_args():
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run plain device-to-device copies of this many GiB (untimed): the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
-    ap.add_argument("--extra", default="", help="comma list of further workloads to time "
-                    "briefly and report under 'other_workloads'")
+    ap.add_argument("--extra", default="gqa70b,long_history,decode_heavy",
+                    help="comma list of further workloads to time briefly and report under "
+                    "'other_workloads' ('none' for none)")
     return ap.parse_args()
 
 
@@ -177,6 +182,19 @@ class DeviceBatch:
         del self.kp, self.vp
 
 
+def recorded_traffic(workload: str, kernel: str):
+    """HBM bytes per launch measured earlier with rocprofv3 --pmc (profiles/traffic.txt), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 6 and f[0] == workload and f[1] == kernel:
+                return int((float(f[2]) * float(f[4]) + float(f[3]) * float(f[5])) * 1024)
+    except OSError:
+        pass
+    return None
+
+
 def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
     attn = {k: v for k, v in ktimes.items() if k in (0, 1)}
     if not attn:
@@ -186,15 +204,16 @@ def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
     t = attn[kind] * 1e-3
     t_hbm = nbytes / (HBM_PEAK_GBPS * 1e9)
     t_mfma = flops / (MFMA_PEAK_TFLOPS * 1e12)
+    traffic = recorded_traffic(db.b.name, KERNEL_NAMES[kind])
     if t_hbm >= t_mfma:
         ach = nbytes / t / 1e9
         return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
                 "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
     ach = flops / t / 1e12
     return {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+            "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
             "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
             "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
 
@@ -291,6 +310,88 @@ def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool
     return res
 
 
+def microbench(ctx_list=(128, 512, 2048, 8192, 16384), reps: int = 30) -> list:
+    """Shape of the paper's Section 6.4 figure (batch 32, query size 8, 40 heads, head size 128,
+    fp16; attention operator only), all four variants built from THIS library's kernel:
+      paged      - KV pages at random places in the pool (what the library is for);
+      contiguous - the same call with every request's pages consecutive ("ideal" layout);
+      copy_out   - first gather the scattered pages into a consecutive region (device copy), then
+                   the contiguous call (the paper's CopyOut+Attention straw-man);
+      multi_round- eight calls of one query token each (the paper's multi-round straw-man)."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    from paper_2312_05516_amd import workloads as wl
+    rows = []
+    for ctx in ctx_list:
+        b = wl.microbench(ctx)
+        bi = wl.microbench(ctx, identity_pages=True)
+        Hq, Hkv, D = b.num_q_heads, b.num_kv_heads, b.head_dim
+        page_elems = Hkv * b.page_size * D
+        kp = wl.random_values((b.num_pages, page_elems), b.dtype, 1, 1.0, "cuda")
+        vp = wl.random_values((b.num_pages, page_elems), b.dtype, 2, 1.0, "cuda")
+        q = wl.random_values((b.total_q, Hq, D), b.dtype, 3, 1.0, "cuda")
+        out = torch.empty_like(q)
+        desc = pv.pool_desc(b.num_pages, Hkv, D, b.dtype)
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+
+        def attn_call(batch, table):
+            plan = pv.plan_create(desc, Hq, batch.ctx_lens, batch.q_lens, batch.max_pages_per_req)
+            pv.plan_upload(plan)
+            ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8,
+                             device="cuda")
+            return plan, ws, (lambda: pv.multi_token_paged_attn_planned(
+                plan, q, kp, vp, table, batch.scale, out, ws))
+
+        t_rand = torch.from_numpy(b.page_table).cuda()
+        t_id = torch.from_numpy(bi.page_table).cuda()
+        plan_r, ws_r, call_r = attn_call(b, t_rand)
+        plan_i, ws_i, call_i = attn_call(bi, t_id)
+        used = torch.from_numpy(b.page_table[b.page_table >= 0].astype(np.int64)).cuda()
+        kc, vc = torch.empty_like(kp), torch.empty_like(vp)
+
+        def copy_out():
+            n = used.numel()
+            torch.index_select(kp, 0, used, out=kc[:n])
+            torch.index_select(vp, 0, used, out=vc[:n])
+            pv.multi_token_paged_attn_planned(plan_i, q, kc, vc, t_id, bi.scale, out, ws_i)
+
+        rounds = []
+        n = int(b.q_lens[0])
+        for i in range(n):
+            pl = pv.plan_create(desc, Hq, b.ctx_lens + i, np.ones_like(b.q_lens),
+                                b.max_pages_per_req)
+            pv.plan_upload(pl)
+            wsr = torch.empty(max(pv.plan_workspace_bytes(pl), 256), dtype=torch.uint8,
+                              device="cuda")
+            qi = q[i::n].contiguous()
+            rounds.append((pl, wsr, qi, torch.empty_like(qi)))
+
+        def multi_round():
+            for pl, wsr, qi, oi in rounds:
+                pv.multi_token_paged_attn_planned(pl, qi, kp, vp, t_rand, b.scale, oi, wsr)
+
+        res = {"ctx": ctx, "paged_ms": round(timed(call_r), 5),
+               "contiguous_ms": round(timed(call_i), 5), "copy_out_ms": round(timed(copy_out), 5),
+               "multi_round_ms": round(timed(multi_round), 5),
+               "kv_GB": round(b.kv_bytes() / 1e9, 4)}
+        res["paged_kv_GBps"] = round(b.kv_bytes() / res["paged_ms"] / 1e6, 1)
+        rows.append(res)
+        torch.cuda.synchronize()
+        for pl in [plan_r, plan_i] + [r[0] for r in rounds]:
+            pl.destroy()
+        del kp, vp, kc, vc
+    return rows
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -302,6 +403,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU (run it under gpurun)", file=sys.stderr)
         sys.exit(1)
+    if args.microbench:
+        print(json.dumps({"metric": "attention call time on the paper's kernel-figure shape "
+                          "(32 requests x 8 query tokens, 40 heads, head size 128, fp16)",
+                          "unit": "ms", "n_gpus": 1, "data": "synthetic",
+                          "microbench": microbench()}))
+        return
     if args.calibration_copy_gib > 0:
         n = int(args.calibration_copy_gib * (1 << 30)) // 4
         src = torch.ones(n, dtype=torch.float32, device="cuda")
@@ -315,7 +422,7 @@ def main():
                             not args.no_graph)
     b = make_batch(args.workload)
     others = []
-    for name in [x for x in args.extra.split(",") if x]:
+    for name in [x for x in args.extra.split(",") if x and x != "none"]:
         r = run_workload(name, max(10, args.steps // 4), max(3, args.warmup // 4), 0, False, 0,
                          False, not args.no_graph)
         others.append({k: r[k] for k in ("workload", "ms_per_step", "tflops", "kv_gbps",
