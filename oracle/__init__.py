@@ -73,6 +73,10 @@ def _bind(lib):
     lib.pvo_attn.argtypes = [dp, ctypes.c_int32, u16p, u16p, u16p, i32p, ctypes.c_int32, i32p,
                              i32p, i32p, ctypes.c_int32, ctypes.c_double, u8p, ctypes.c_int32,
                              ctypes.c_int32, f64p, ctypes.c_int32, ctypes.c_int32, f64p, i32p]
+    lib.pvo_pages_gather.restype = ctypes.c_int
+    lib.pvo_pages_gather.argtypes = [dp, u16p, u16p, i32p, ctypes.c_int32, u16p]
+    lib.pvo_pages_scatter.restype = ctypes.c_int
+    lib.pvo_pages_scatter.argtypes = [dp, u16p, i32p, ctypes.c_int32, u16p, u16p]
     return lib
 
 
@@ -191,3 +195,31 @@ def attn(pool, num_q_heads, q, k_pages, v_pages, page_table, ctx_lens, q_lens, q
     if probs_of is not None:
         return out, probs, info
     return out, info
+
+
+def pages_gather(pool, k_pages, v_pages, page_ids):
+    """Staging image [n, 2, page_elems] (uint16) of the listed pages: K image then V image."""
+    lib = _load()
+    desc = _desc(*pool)
+    ids = _i32(page_ids)
+    page_elems = pool[2] * pool[1] * pool[3]
+    staging = np.zeros((len(ids), 2, page_elems), dtype=np.uint16)
+    rc = lib.pvo_pages_gather(ctypes.byref(desc), _p(k_pages, ctypes.c_uint16),
+                              _p(v_pages, ctypes.c_uint16), _p(ids, ctypes.c_int32), len(ids),
+                              _p(staging, ctypes.c_uint16))
+    _check(rc, "pages_gather")
+    return staging
+
+
+def pages_scatter(pool, staging, page_ids, k_pages, v_pages):
+    """Write a staging image back into the listed pages of the pools IN PLACE."""
+    lib = _load()
+    desc = _desc(*pool)
+    ids = _i32(page_ids)
+    staging = np.ascontiguousarray(staging, dtype=np.uint16)
+    assert k_pages.dtype == np.uint16 and k_pages.flags.c_contiguous
+    assert v_pages.dtype == np.uint16 and v_pages.flags.c_contiguous
+    rc = lib.pvo_pages_scatter(ctypes.byref(desc), _p(staging, ctypes.c_uint16),
+                               _p(ids, ctypes.c_int32), len(ids), _p(k_pages, ctypes.c_uint16),
+                               _p(v_pages, ctypes.c_uint16))
+    _check(rc, "pages_scatter")

@@ -237,3 +237,42 @@ int pvo_attn(const pvo_pool_desc *p, int32_t num_q_heads, const uint16_t *q,
     if (threads_used) *threads_used = team;
     return status;
 }
+
+/*
+ * Tier swapping (paper Section 4.3.2 "ahead-of-time swapping" and 4.3.3 "pipelined KV-cache
+ * recovery"): KV-tokens leave the GPU pool for a CPU cache and come back in whole pages.  The
+ * staging buffer holds, for the i-th listed page, that page's K image followed by its V image
+ * (each num_kv_heads * page_size * head_dim 16-bit elements, exactly as they lie in the pools).
+ * Pure copies.
+ */
+int pvo_pages_gather(const pvo_pool_desc *p, const uint16_t *k_pages, const uint16_t *v_pages,
+                     const int32_t *page_ids, int32_t n, uint16_t *staging)
+{
+    if (!pvo_desc_ok(p) || n < 0) return PVO_BAD_ARG;
+    const int64_t page_elems = (int64_t)p->num_kv_heads * p->page_size * p->head_dim;
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t page = page_ids[i];
+        if (page < 0 || page >= p->num_pages) return PVO_BAD_PAGE;
+        for (int64_t e = 0; e < page_elems; ++e) {
+            staging[(2 * (int64_t)i) * page_elems + e] = k_pages[page * page_elems + e];
+            staging[(2 * (int64_t)i + 1) * page_elems + e] = v_pages[page * page_elems + e];
+        }
+    }
+    return PVO_OK;
+}
+
+int pvo_pages_scatter(const pvo_pool_desc *p, const uint16_t *staging, const int32_t *page_ids,
+                      int32_t n, uint16_t *k_pages, uint16_t *v_pages)
+{
+    if (!pvo_desc_ok(p) || n < 0) return PVO_BAD_ARG;
+    const int64_t page_elems = (int64_t)p->num_kv_heads * p->page_size * p->head_dim;
+    for (int32_t i = 0; i < n; ++i) {
+        const int64_t page = page_ids[i];
+        if (page < 0 || page >= p->num_pages) return PVO_BAD_PAGE;
+        for (int64_t e = 0; e < page_elems; ++e) {
+            k_pages[page * page_elems + e] = staging[(2 * (int64_t)i) * page_elems + e];
+            v_pages[page * page_elems + e] = staging[(2 * (int64_t)i + 1) * page_elems + e];
+        }
+    }
+    return PVO_OK;
+}

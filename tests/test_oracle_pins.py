@@ -393,3 +393,43 @@ def test_unit_mask_selects_units(oracle):
     assert np.isnan(part[0:3, 0:2]).all() and np.isnan(part[3:5, 2:4]).all()
     assert np.array_equal(part[0:3, 2:4], full[0:3, 2:4])
     assert np.array_equal(part[3:5, 0:2], full[3:5, 0:2])
+
+
+# ---------------------------------------------------------------- tier swapping (page copies)
+def test_page_gather_scatter_are_plain_copies(oracle):
+    b = wl.custom([100, 30], [5, 2], num_q_heads=4, num_kv_heads=2, head_dim=64, seed=41)
+    case = H.make_case(b, fill="random")
+    pool = H.pool_tuple(b)
+    page_elems = b.num_kv_heads * b.page_size * b.head_dim
+    kp = case.k_pool1.reshape(b.num_pages, page_elems)
+    vp = case.v_pool1.reshape(b.num_pages, page_elems)
+    rng = np.random.default_rng(3)
+    ids = rng.permutation(b.num_pages)[:7].astype(np.int32)
+    st = oracle.pages_gather(pool, case.k_pool1, case.v_pool1, ids)
+    assert st.shape == (7, 2, page_elems)
+    assert np.array_equal(st[:, 0], kp[ids]) and np.array_equal(st[:, 1], vp[ids])  # numpy indexing
+    # scatter into other pages of a fresh pool: listed pages take the image, the rest is untouched
+    k2 = np.full_like(case.k_pool1, 0x1234)
+    v2 = np.full_like(case.v_pool1, 0x4321)
+    dst = rng.permutation(b.num_pages)[:7].astype(np.int32)
+    oracle.pages_scatter(pool, st, dst, k2, v2)
+    k2r, v2r = k2.reshape(b.num_pages, page_elems), v2.reshape(b.num_pages, page_elems)
+    assert np.array_equal(k2r[dst], kp[ids]) and np.array_equal(v2r[dst], vp[ids])
+    rest = np.setdiff1d(np.arange(b.num_pages), dst)
+    assert (k2r[rest] == 0x1234).all() and (v2r[rest] == 0x4321).all()
+    # swap out + swap in to new places + remapped table = same attention result, bit for bit
+    base, _ = run_oracle(oracle, case)
+    used = np.unique(b.page_table[b.page_table >= 0])
+    new_home = rng.permutation(b.num_pages)[:len(used)].astype(np.int32)
+    st = oracle.pages_gather(pool, case.k_pool1, case.v_pool1, used.astype(np.int32))
+    k3 = np.zeros_like(case.k_pool1)
+    v3 = np.zeros_like(case.v_pool1)
+    oracle.pages_scatter(pool, st, new_home, k3, v3)
+    remap = np.full(b.num_pages, -1, dtype=np.int32)
+    remap[used] = new_home
+    table = np.where(b.page_table >= 0, remap[np.maximum(b.page_table, 0)], -1).astype(np.int32)
+    got, _ = oracle.attn(pool, b.num_q_heads, case.q, k3, v3, table, b.ctx_lens, b.q_lens,
+                         b.q_start, b.scale)
+    assert np.array_equal(got, base)
+    with pytest.raises(RuntimeError):
+        oracle.pages_gather(pool, case.k_pool1, case.v_pool1, [b.num_pages])
