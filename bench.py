@@ -46,6 +46,9 @@ def parse_args():
                     help="instead of the step benchmark, time the attention call on the shape of the "
                     "paper's kernel figure (32 requests x 8 query tokens, context sweep) against our "
                     "own contiguous, copy-out and one-token-per-round variants")
+    ap.add_argument("--swap", action="store_true",
+                    help="instead of the step benchmark, time page gather / scatter (tier swapping) "
+                    "through device staging and through pinned host memory")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying one captured HIP graph "
                     "per KV pool (the step of a small batch is otherwise bound by host launch time)")
@@ -392,6 +395,50 @@ def microbench(ctx_list=(128, 512, 2048, 8192, 16384), reps: int = 30) -> list:
     return rows
 
 
+def swap_bench(reps: int = 20) -> dict:
+    """Page gather / scatter of 32-token chunks (two pages) picked at random from a pool shaped like
+    the decode-heavy configuration (40 KV heads, head size 128, fp16: 160 KiB per K page)."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    from paper_2312_05516_amd import workloads as wl
+    Hkv, D, dtype = 40, 128, "f16"
+    num_pages, n = 16384, 4096  # 2.7 GB of K+V in the pool, 1.3 GB moved per call
+    page_elems = Hkv * 16 * D
+    desc = pv.pool_desc(num_pages, Hkv, D, dtype)
+    kp = wl.random_values((num_pages, page_elems), dtype, 1, 1.0, "cuda")
+    vp = wl.random_values((num_pages, page_elems), dtype, 2, 1.0, "cuda")
+    rng = np.random.default_rng(7)
+    chunks = rng.permutation(num_pages // 2)[:n // 2]
+    ids = torch.from_numpy(np.stack([2 * chunks, 2 * chunks + 1], 1).ravel().astype(np.int32)).cuda()
+    moved = 2 * n * page_elems * 2  # K and V bytes per call
+    dev = torch.empty((n, 2, page_elems), dtype=torch.int16, device="cuda")
+    host = torch.empty((n, 2, page_elems), dtype=torch.int16).pin_memory()
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    t = {"gather_device": timed(lambda: pv.pages_gather(desc, kp, vp, ids, n, dev)),
+         "scatter_device": timed(lambda: pv.pages_scatter(desc, dev, ids, n, kp, vp)),
+         "gather_pinned_host": timed(lambda: pv.pages_gather(desc, kp, vp, ids, n, host)),
+         "scatter_pinned_host": timed(lambda: pv.pages_scatter(desc, host, ids, n, kp, vp))}
+    res = {"pages": n, "bytes_moved": moved}
+    for k, v in t.items():
+        res[k + "_ms"] = round(v * 1e3, 4)
+        res[k + "_GBps"] = round(moved / v / 1e9, 1)
+    # device staging reads and writes HBM: 2 x moved bytes against 8 TB/s
+    res["roofline_device"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBPS,
+                              "achieved": round(2 * moved / t["gather_device"] / 1e9, 1),
+                              "frac": round(2 * moved / t["gather_device"] / 1e9 / HBM_PEAK_GBPS, 4)}
+    return res
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -408,6 +455,11 @@ def main():
                           "(32 requests x 8 query tokens, 40 heads, head size 128, fp16)",
                           "unit": "ms", "n_gpus": 1, "data": "synthetic",
                           "microbench": microbench()}))
+        return
+    if args.swap:
+        print(json.dumps({"metric": "page gather/scatter for tier swapping (chunks of two 16-token "
+                          "pages, 40 KV heads x head size 128, fp16)", "unit": "GB/s", "n_gpus": 1,
+                          "data": "synthetic", "swap": swap_bench()}))
         return
     if args.calibration_copy_gib > 0:
         n = int(args.calibration_copy_gib * (1 << 30)) // 4

@@ -211,6 +211,27 @@ pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_head
                                     int32_t total_q, float scale, void *out, void *workspace,
                                     size_t workspace_bytes, void *stream);
 
+/*
+ * Page gather / scatter for tier swapping (paper Section 4.3.2: KV-tokens are copied out to a CPU
+ * cache ahead of time; Section 4.3.3: they are copied back layer by layer, and a layer's attention
+ * starts once its KV-tokens have landed).  Whole pages move between the pools and a staging buffer:
+ * for the i-th listed page the staging buffer holds that page's K image (num_kv_heads*16*D
+ * elements, exactly as in the pool) followed by its V image, i.e. 2*pv_pool_bytes/num_pages bytes
+ * per page.  Pure copies (bit-exact); pages that are not listed are not touched.
+ *   page_ids : device int32 [n]; every id must be in [0, num_pages) and, for the scatter, distinct
+ *              (not checked by these calls)
+ *   staging  : device memory, or pinned host memory the GPU can address (e.g. hipHostMalloc): then
+ *              the copy crosses PCIe inside the kernel; 16-byte aligned
+ * Asynchronous on `stream`; record an event after a scatter and make the attention stream wait for
+ * it to get the paper's per-layer gating.
+ */
+pv_status pv_pages_gather(const pv_pool_desc *pool, const void *k_pages, const void *v_pages,
+                          const int32_t *page_ids /* device */, int32_t n, void *staging,
+                          void *stream);
+pv_status pv_pages_scatter(const pv_pool_desc *pool, const void *staging,
+                           const int32_t *page_ids /* device */, int32_t n, void *k_pages,
+                           void *v_pages, void *stream);
+
 /* Upper bound of the workspace the one-shot attention call can need for such a batch. */
 size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, int32_t num_reqs,
                                int32_t total_q, int32_t max_kv_len);

@@ -34,6 +34,7 @@ EXPORTS = [
     "pv_plan_check_page_table", "pv_plan_enable_timing", "pv_plan_kernel_ms",
     "pv_kv_append_planned", "pv_multi_token_paged_attn_planned",
     "pv_kv_append", "pv_multi_token_paged_attn", "pv_attn_workspace_bytes",
+    "pv_pages_gather", "pv_pages_scatter",
 ]
 
 
@@ -103,6 +104,10 @@ _lib.pv_multi_token_paged_attn.argtypes = [_descp, ctypes.c_int32, _vp, _vp, _vp
                                            ctypes.c_int32, _i32p, _i32p, _i32p, ctypes.c_int32,
                                            ctypes.c_int32, ctypes.c_float, _vp, _vp,
                                            ctypes.c_size_t, _vp]
+_lib.pv_pages_gather.restype = ctypes.c_int
+_lib.pv_pages_gather.argtypes = [_descp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp]
+_lib.pv_pages_scatter.restype = ctypes.c_int
+_lib.pv_pages_scatter.argtypes = [_descp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp]
 _lib.pv_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.pv_attn_workspace_bytes.argtypes = [_descp] + [ctypes.c_int32] * 4
 
@@ -304,3 +309,14 @@ def attn_workspace_bytes(desc: PoolDesc, num_q_heads: int, num_reqs: int, total_
                          max_kv_len: int) -> int:
     return int(_lib.pv_attn_workspace_bytes(ctypes.byref(desc), int(num_q_heads), int(num_reqs),
                                             int(total_q), int(max_kv_len)))
+
+
+def pages_gather(desc: PoolDesc, k_pages, v_pages, page_ids, n: int, staging, stream=None):
+    _check(_lib.pv_pages_gather(ctypes.byref(desc), _ptr(k_pages), _ptr(v_pages), _ptr(page_ids),
+                                int(n), _ptr(staging), _stream(stream)), "pv_pages_gather")
+
+
+def pages_scatter(desc: PoolDesc, staging, page_ids, n: int, k_pages, v_pages, stream=None):
+    _check(_lib.pv_pages_scatter(ctypes.byref(desc), _ptr(staging), _ptr(page_ids), int(n),
+                                 _ptr(k_pages), _ptr(v_pages), _stream(stream)),
+           "pv_pages_scatter")

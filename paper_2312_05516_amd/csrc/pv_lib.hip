@@ -21,6 +21,10 @@ hipError_t launch_attn_wide(const pv_plan *plan, const void *q, const void *k_pa
 hipError_t launch_attn_combine(const pv_plan *plan, const float *ws_o, const float *ws_ml,
                                void *out, hipStream_t stream);
 
+hipError_t launch_pages_copy(bool gather, const pv_pool_desc *pool, const int32_t *page_ids,
+                             int32_t n, void *k_pages, void *v_pages, void *staging,
+                             hipStream_t stream);
+
 static std::mutex g_upload_mutex;
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -293,6 +297,34 @@ pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_head
         s = PV_ERR_HIP;
     pv_plan_destroy(plan);
     return s;
+}
+
+static pv_status pages_copy(bool gather, const pv_pool_desc *pool, const int32_t *page_ids,
+                            int32_t n, void *k_pages, void *v_pages, void *staging, void *stream)
+{
+    pv_status why;
+    if (!pv::pool_desc_valid(pool, &why)) return why;
+    if (n < 0) return PV_ERR_INVALID_ARG;
+    if (n == 0) return PV_OK;
+    if (!page_ids || !k_pages || !v_pages || !staging) return PV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(staging) & 15u) != 0) return PV_ERR_INVALID_ARG;
+    hipError_t e = pv::launch_pages_copy(gather, pool, page_ids, n, k_pages, v_pages, staging,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PV_OK : PV_ERR_HIP;
+}
+
+pv_status pv_pages_gather(const pv_pool_desc *pool, const void *k_pages, const void *v_pages,
+                          const int32_t *page_ids, int32_t n, void *staging, void *stream)
+{
+    return pages_copy(true, pool, page_ids, n, const_cast<void *>(k_pages),
+                      const_cast<void *>(v_pages), staging, stream);
+}
+
+pv_status pv_pages_scatter(const pv_pool_desc *pool, const void *staging, const int32_t *page_ids,
+                           int32_t n, void *k_pages, void *v_pages, void *stream)
+{
+    return pages_copy(false, pool, page_ids, n, k_pages, v_pages, const_cast<void *>(staging),
+                      stream);
 }
 
 size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, int32_t num_reqs,

@@ -1,0 +1,115 @@
+"""Page gather / scatter (tier swapping) through the C ABI against the oracle: bit-exact copies,
+device and pinned-host staging, and the per-layer event gating the paper describes."""
+import numpy as np
+import pytest
+
+import helpers as H
+from paper_2312_05516_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(b, seed=0):
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    case = H.make_case(b, fill="random")
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    kp, vp = H.to_dev_bits(case.k_pool1, b.dtype), H.to_dev_bits(case.v_pool1, b.dtype)
+    return torch, pv, case, desc, kp, vp
+
+
+@pytest.mark.parametrize("heads,d,dt", [(2, 64, "f16"), (5, 128, "bf16"), (1, 64, "bf16")])
+def test_gather_scatter_device_staging(oracle, heads, d, dt):
+    b = wl.custom([100, 30, 260], [5, 2, 1], num_q_heads=heads, num_kv_heads=heads, head_dim=d,
+                  dtype=dt, seed=73)
+    torch, pv, case, desc, kp, vp = _setup(b)
+    page_elems = b.num_kv_heads * b.page_size * b.head_dim
+    rng = np.random.default_rng(1)
+    ids = rng.permutation(b.num_pages)[:11].astype(np.int32)
+    ids_d = torch.from_numpy(ids).cuda()
+    staging = torch.zeros((len(ids), 2, page_elems), dtype=torch.int16, device="cuda")
+    pv.pages_gather(desc, kp, vp, ids_d, len(ids), staging)
+    torch.cuda.synchronize()
+    want = oracle.pages_gather(H.pool_tuple(b), case.k_pool1, case.v_pool1, ids)
+    assert np.array_equal(staging.cpu().numpy().view(np.uint16), want)
+    # scatter into different pages of pools filled with a marker
+    k2 = torch.full_like(kp.view(torch.int16), 0x1234)
+    v2 = torch.full_like(vp.view(torch.int16), 0x4321)
+    dst = rng.permutation(b.num_pages)[:11].astype(np.int32)
+    pv.pages_scatter(desc, staging, torch.from_numpy(dst).cuda(), len(dst), k2, v2)
+    torch.cuda.synchronize()
+    wk = np.full(wl.pool_elems(b), 0x1234, dtype=np.uint16)
+    wv = np.full(wl.pool_elems(b), 0x4321, dtype=np.uint16)
+    oracle.pages_scatter(H.pool_tuple(b), want, dst, wk, wv)
+    assert np.array_equal(k2.cpu().numpy().view(np.uint16).ravel(), wk)
+    assert np.array_equal(v2.cpu().numpy().view(np.uint16).ravel(), wv)
+    # n = 0 is a no-op
+    pv.pages_gather(desc, kp, vp, ids_d, 0, staging)
+
+
+def test_swap_through_pinned_host_memory_and_event_gated_attention(oracle):
+    """Swap every page of a batch out to pinned host memory, bring it back into other pages on a
+    side stream, and let the attention stream wait for the event recorded after the swap-in."""
+    b = wl.custom([300, 45, 700], [1, 20, 3], num_q_heads=8, num_kv_heads=2, head_dim=128,
+                  dtype="f16", seed=79)
+    torch, pv, case, desc, kp, vp = _setup(b)
+    page_elems = b.num_kv_heads * b.page_size * b.head_dim
+    used = np.unique(b.page_table[b.page_table >= 0]).astype(np.int32)
+    host = torch.zeros((len(used), 2, page_elems), dtype=torch.int16).pin_memory()
+    pv.pages_gather(desc, kp, vp, torch.from_numpy(used).cuda(), len(used), host)
+    torch.cuda.synchronize()
+    want = oracle.pages_gather(H.pool_tuple(b), case.k_pool1, case.v_pool1, used)
+    assert np.array_equal(host.numpy().view(np.uint16), want)
+
+    rng = np.random.default_rng(2)
+    new_home = rng.permutation(b.num_pages)[:len(used)].astype(np.int32)
+    remap = np.full(b.num_pages, -1, dtype=np.int32)
+    remap[used] = new_home
+    table_h = np.where(b.page_table >= 0, remap[np.maximum(b.page_table, 0)], -1).astype(np.int32)
+    k2 = torch.zeros_like(kp)
+    v2 = torch.zeros_like(vp)
+    table = torch.from_numpy(table_h).cuda()
+    q = H.to_dev_bits(case.q, b.dtype)
+    out = torch.zeros((b.total_q, b.num_q_heads, b.head_dim), dtype=q.dtype, device="cuda")
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
+    home_d = torch.from_numpy(new_home).cuda()
+    torch.cuda.synchronize()
+    copy_stream = torch.cuda.Stream()
+    landed = torch.cuda.Event()
+    with torch.cuda.stream(copy_stream):
+        pv.pages_scatter(desc, host, home_d, len(used), k2, v2)
+        landed.record(copy_stream)
+    torch.cuda.current_stream().wait_event(landed)  # the layer's attention waits for its KV
+    pv.multi_token_paged_attn_planned(plan, q, k2, v2, table, b.scale, out, ws)
+    torch.cuda.synchronize()
+    plan.destroy()
+    got = H.bits_to_f64(H.from_dev_bits(out), b.dtype)
+    ref, _ = oracle.attn(H.pool_tuple(b), b.num_q_heads, case.q, case.k_pool1, case.v_pool1,
+                         b.page_table, b.ctx_lens, b.q_lens, b.q_start, b.scale)
+    assert np.abs(got - ref).max() <= H.TOL[b.dtype]
+    # and it is bit-identical to attention on the pages where they were before the swap
+    out0 = torch.zeros_like(out)
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.multi_token_paged_attn_planned(plan, q, kp, vp, torch.from_numpy(b.page_table).cuda(),
+                                      b.scale, out0, ws)
+    torch.cuda.synchronize()
+    plan.destroy()
+    assert np.array_equal(H.from_dev_bits(out0), H.from_dev_bits(out))
+
+
+def test_swap_rejects_bad_arguments():
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    desc = pv.pool_desc(8, 2, 64, "f16")
+    buf = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
+    ids = torch.zeros(4, dtype=torch.int32, device="cuda")
+    with pytest.raises(pv.PvError) as e:
+        pv.pages_gather(desc, buf, buf, ids, -1, buf)
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:
+        pv.pages_gather(desc, buf, buf, None, 2, buf)
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:
+        pv.pages_scatter(pv.pool_desc(8, 2, 80, "f16"), buf, ids, 2, buf, buf)
+    assert e.value.status == 2
