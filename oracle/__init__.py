@@ -73,6 +73,10 @@ def _bind(lib):
     lib.pvo_attn.argtypes = [dp, ctypes.c_int32, u16p, u16p, u16p, i32p, ctypes.c_int32, i32p,
                              i32p, i32p, ctypes.c_int32, ctypes.c_double, u8p, ctypes.c_int32,
                              ctypes.c_int32, f64p, ctypes.c_int32, ctypes.c_int32, f64p, i32p]
+    lib.pvo_cost.restype = ctypes.c_double
+    lib.pvo_cost.argtypes = [i32p, f64p, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
+    lib.pvo_retention_order.restype = ctypes.c_int
+    lib.pvo_retention_order.argtypes = [f64p, f64p, ctypes.c_int32, i32p]
     lib.pvo_pages_gather.restype = ctypes.c_int
     lib.pvo_pages_gather.argtypes = [dp, u16p, u16p, i32p, ctypes.c_int32, u16p]
     lib.pvo_pages_scatter.restype = ctypes.c_int
@@ -223,3 +227,24 @@ def pages_scatter(pool, staging, page_ids, k_pages, v_pages):
                                _p(ids, ctypes.c_int32), len(ids), _p(k_pages, ctypes.c_uint16),
                                _p(v_pages, ctypes.c_uint16))
     _check(rc, "pages_scatter")
+
+
+def cost(ctx_points, attn_cost, c_other, l) -> float:
+    """Cost(l) = interpolated attention cost + c (eviction policy's recomputation cost)."""
+    lib = _load()
+    pts = _i32(ctx_points)
+    ys = np.ascontiguousarray(attn_cost, dtype=np.float64)
+    return float(lib.pvo_cost(_p(pts, ctypes.c_int32), _p(ys, ctypes.c_double), len(pts),
+                              float(c_other), int(l)))
+
+
+def retention_order(cost_values, idle_time) -> np.ndarray:
+    """Chunk indices in eviction order: ascending V = cost / idle_time."""
+    lib = _load()
+    c = np.ascontiguousarray(cost_values, dtype=np.float64)
+    t = np.ascontiguousarray(idle_time, dtype=np.float64)
+    assert c.shape == t.shape and c.ndim == 1
+    order = np.zeros(len(c), dtype=np.int32)
+    _check(lib.pvo_retention_order(_p(c, ctypes.c_double), _p(t, ctypes.c_double), len(c),
+                                   _p(order, ctypes.c_int32)), "retention_order")
+    return order

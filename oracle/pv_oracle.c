@@ -276,3 +276,44 @@ int pvo_pages_scatter(const pvo_pool_desc *p, const uint16_t *staging, const int
     }
     return PVO_OK;
 }
+
+/*
+ * Recomputation-cost model of the eviction policy (paper Section 4.3.1).  The cost of recomputing
+ * a 32-token chunk whose attention spans a context of l tokens is Cost(l) = Cost_attention(l) + c,
+ * with Cost_attention profiled at a few context sizes (powers of two) and interpolated in between
+ * (linearly here; beyond the profiled range the nearest segment is extended); the retention value
+ * of a chunk is V = Cost(l) / T with T the time since its conversation was last active, and chunks
+ * are evicted in ascending order of V.
+ */
+double pvo_cost(const int32_t *ctx_points, const double *attn_cost, int32_t n, double c_other,
+                int32_t l)
+{
+    if (n <= 0) return c_other;
+    if (n == 1) return attn_cost[0] + c_other;
+    int32_t k = 0; /* segment [k, k+1] used for l */
+    while (k + 2 < n && l > ctx_points[k + 1]) ++k;
+    const double x0 = ctx_points[k], x1 = ctx_points[k + 1];
+    const double y0 = attn_cost[k], y1 = attn_cost[k + 1];
+    return y0 + (y1 - y0) * ((double)l - x0) / (x1 - x0) + c_other;
+}
+
+/* order_out = chunk indices by ascending V = cost / idle_time (ties: lower index first). */
+int pvo_retention_order(const double *cost, const double *idle_time, int32_t n, int32_t *order_out)
+{
+    if (n < 0) return PVO_BAD_ARG;
+    for (int32_t i = 0; i < n; ++i) {
+        if (!(idle_time[i] > 0.0)) return PVO_BAD_ARG;
+        order_out[i] = i;
+    }
+    for (int32_t i = 1; i < n; ++i) { /* insertion sort: plain and stable */
+        const int32_t cur = order_out[i];
+        const double v = cost[cur] / idle_time[cur];
+        int32_t j = i - 1;
+        while (j >= 0 && cost[order_out[j]] / idle_time[order_out[j]] > v) {
+            order_out[j + 1] = order_out[j];
+            --j;
+        }
+        order_out[j + 1] = cur;
+    }
+    return PVO_OK;
+}

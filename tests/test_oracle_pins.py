@@ -433,3 +433,27 @@ def test_page_gather_scatter_are_plain_copies(oracle):
     assert np.array_equal(got, base)
     with pytest.raises(RuntimeError):
         oracle.pages_gather(pool, case.k_pool1, case.v_pool1, [b.num_pages])
+
+
+# ---------------------------------------------------------------- eviction cost model
+def test_cost_interpolation_and_retention_order(oracle):
+    pts = [32, 64, 128, 256, 512]
+    ys = [1.0, 1.5, 2.5, 4.5, 8.5]
+    for p, y in zip(pts, ys):  # profiled points are reproduced exactly (+ c)
+        assert oracle.cost(pts, ys, 0.25, p) == y + 0.25
+    assert oracle.cost(pts, ys, 0.0, 96) == 2.0  # midway between 64 and 128
+    assert oracle.cost(pts, ys, 0.0, 192) == 3.5
+    assert np.isclose(oracle.cost(pts, ys, 0.0, np.interp(1, [0, 1], [300, 300])),
+                      np.interp(300, pts, ys))  # numpy's piecewise-linear interpolation
+    assert np.isclose(oracle.cost(pts, ys, 0.0, 1024), 8.5 + (8.5 - 4.5) * 2)  # last segment extended
+    assert np.isclose(oracle.cost(pts, ys, 0.0, 16), 1.0 - 0.25)  # first segment extended
+    rng = np.random.default_rng(0)
+    c = rng.uniform(1, 10, size=50)
+    t = rng.uniform(1, 600, size=50)
+    order = oracle.retention_order(c, t)
+    assert np.array_equal(order, np.argsort(c / t, kind="stable"))
+    # same idle time: cheaper (earlier, shorter-context) chunks go first; same cost: older first
+    assert oracle.retention_order([3, 1, 2], [5, 5, 5]).tolist() == [1, 2, 0]
+    assert oracle.retention_order([2, 2, 2], [10, 300, 60]).tolist() == [1, 2, 0]
+    with pytest.raises(RuntimeError):
+        oracle.retention_order([1.0], [0.0])
