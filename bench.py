@@ -46,6 +46,10 @@ def parse_args():
                     help="instead of the step benchmark, time the attention call on the shape of the "
                     "paper's kernel figure (32 requests x 8 query tokens, context sweep) against our "
                     "own contiguous, copy-out and one-token-per-round variants")
+    ap.add_argument("--cost-profile", action="store_true",
+                    help="instead of the step benchmark, measure the attention cost of one 32-token "
+                    "chunk at power-of-two context sizes (the profile the paper's eviction policy "
+                    "interpolates) and check the library's interpolation at the midpoints")
     ap.add_argument("--swap", action="store_true",
                     help="instead of the step benchmark, time page gather / scatter (tier swapping) "
                     "through device staging and through pinned host memory")
@@ -395,6 +399,49 @@ def microbench(ctx_list=(128, 512, 2048, 8192, 16384), reps: int = 30) -> list:
     return rows
 
 
+def cost_profile(reps: int = 50) -> dict:
+    """Cost_attention(l) of the eviction policy (paper Section 4.3.1): attention time of one
+    32-token chunk whose context (itself included) is l tokens, 40 heads x head size 128, fp16, at
+    powers of two; then the library's interpolated cost at the midpoints next to a measurement."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    from paper_2312_05516_amd import workloads as wl
+
+    def measure(l: int) -> float:
+        b = wl.custom([l - 32], [32], num_q_heads=40, num_kv_heads=40, head_dim=128, dtype="f16",
+                      seed=l, name=f"chunk_l{l}")
+        page_elems = 40 * 16 * 128
+        kp = wl.random_values((b.num_pages, page_elems), b.dtype, 1, 1.0, "cuda")
+        vp = wl.random_values((b.num_pages, page_elems), b.dtype, 2, 1.0, "cuda")
+        q = wl.random_values((32, 40, 128), b.dtype, 3, 1.0, "cuda")
+        out = torch.empty_like(q)
+        table = torch.from_numpy(b.page_table).cuda()
+        desc = pv.pool_desc(b.num_pages, 40, 128, b.dtype)
+        plan = pv.plan_create(desc, 40, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        pv.plan_upload(plan)
+        ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            pv.multi_token_paged_attn_planned(plan, q, kp, vp, table, b.scale, out, ws)
+        torch.cuda.synchronize()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(reps):
+            pv.multi_token_paged_attn_planned(plan, q, kp, vp, table, b.scale, out, ws)
+        stop.record()
+        torch.cuda.synchronize()
+        plan.destroy()
+        return start.elapsed_time(stop) / reps
+
+    points = [2 ** k for k in range(5, 16)]  # 32 .. 32768
+    costs = [measure(l) for l in points]
+    checks = []
+    for l in (48, 3000, 24000):
+        checks.append({"l": l, "interpolated_ms": round(pv.cost_model(points, costs, 0.0, l), 5),
+                       "measured_ms": round(measure(l), 5)})
+    return {"ctx_points": points, "attn_cost_ms": [round(c, 5) for c in costs],
+            "interpolation_checks": checks}
+
+
 def swap_bench(reps: int = 20) -> dict:
     """Page gather / scatter of 32-token chunks (two pages) picked at random from a pool shaped like
     the decode-heavy configuration (40 KV heads, head size 128, fp16: 160 KiB per K page)."""
@@ -455,6 +502,11 @@ def main():
                           "(32 requests x 8 query tokens, 40 heads, head size 128, fp16)",
                           "unit": "ms", "n_gpus": 1, "data": "synthetic",
                           "microbench": microbench()}))
+        return
+    if args.cost_profile:
+        print(json.dumps({"metric": "attention cost of one 32-token chunk vs context size "
+                          "(40 heads, head size 128, fp16)", "unit": "ms", "n_gpus": 1,
+                          "data": "synthetic", "cost_profile": cost_profile()}))
         return
     if args.swap:
         print(json.dumps({"metric": "page gather/scatter for tier swapping (chunks of two 16-token "

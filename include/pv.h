@@ -232,6 +232,24 @@ pv_status pv_pages_scatter(const pv_pool_desc *pool, const void *staging,
                            const int32_t *page_ids /* device */, int32_t n, void *k_pages,
                            void *v_pages, void *stream);
 
+/*
+ * Recomputation-cost model of the eviction policy (paper Section 4.3.1).  Pure host code.
+ * Cost(l) = Cost_attention(l) + c_other is the cost of recomputing one 32-token chunk whose
+ * attention spans l context tokens; Cost_attention is profiled at a few context sizes (the paper
+ * uses powers of two; `bench.py --cost-profile` measures it with this library's kernel) and
+ * interpolated linearly in between, the first / last segment being extended outside the range.
+ *   ctx_points : host, strictly ascending context sizes [n];  attn_cost : host [n]
+ * pv_cost_model returns Cost(l) (c_other alone when n == 0, attn_cost[0] + c_other when n == 1);
+ * NaN on a null pointer with n > 0.
+ * pv_retention_order writes the chunk indices in eviction order, i.e. ascending retention value
+ * V = cost[i] / idle_time[i] (idle_time = time since the chunk's conversation was last active,
+ * > 0; ties keep the lower index first).  PV_ERR_INVALID_ARG on null pointers or idle_time <= 0.
+ */
+double pv_cost_model(const int32_t *ctx_points, const double *attn_cost, int32_t n, double c_other,
+                     int32_t l);
+pv_status pv_retention_order(const double *cost, const double *idle_time, int32_t n,
+                             int32_t *order_out);
+
 /* Upper bound of the workspace the one-shot attention call can need for such a batch. */
 size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, int32_t num_reqs,
                                int32_t total_q, int32_t max_kv_len);

@@ -34,7 +34,7 @@ EXPORTS = [
     "pv_plan_check_page_table", "pv_plan_enable_timing", "pv_plan_kernel_ms",
     "pv_kv_append_planned", "pv_multi_token_paged_attn_planned",
     "pv_kv_append", "pv_multi_token_paged_attn", "pv_attn_workspace_bytes",
-    "pv_pages_gather", "pv_pages_scatter",
+    "pv_pages_gather", "pv_pages_scatter", "pv_cost_model", "pv_retention_order",
 ]
 
 
@@ -108,6 +108,11 @@ _lib.pv_pages_gather.restype = ctypes.c_int
 _lib.pv_pages_gather.argtypes = [_descp, _vp, _vp, _vp, ctypes.c_int32, _vp, _vp]
 _lib.pv_pages_scatter.restype = ctypes.c_int
 _lib.pv_pages_scatter.argtypes = [_descp, _vp, _vp, ctypes.c_int32, _vp, _vp, _vp]
+_f64p = ctypes.POINTER(ctypes.c_double)
+_lib.pv_cost_model.restype = ctypes.c_double
+_lib.pv_cost_model.argtypes = [_i32p, _f64p, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
+_lib.pv_retention_order.restype = ctypes.c_int
+_lib.pv_retention_order.argtypes = [_f64p, _f64p, ctypes.c_int32, _i32p]
 _lib.pv_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.pv_attn_workspace_bytes.argtypes = [_descp] + [ctypes.c_int32] * 4
 
@@ -320,3 +325,21 @@ def pages_scatter(desc: PoolDesc, staging, page_ids, n: int, k_pages, v_pages, s
     _check(_lib.pv_pages_scatter(ctypes.byref(desc), _ptr(staging), _ptr(page_ids), int(n),
                                  _ptr(k_pages), _ptr(v_pages), _stream(stream)),
            "pv_pages_scatter")
+
+
+def cost_model(ctx_points, attn_cost, c_other: float, l: int) -> float:
+    pts = _host_i32(ctx_points)
+    ys = np.ascontiguousarray(attn_cost, dtype=np.float64)
+    return float(_lib.pv_cost_model(_i32(pts), ys.ctypes.data_as(_f64p), len(pts), float(c_other),
+                                    int(l)))
+
+
+def retention_order(cost, idle_time) -> np.ndarray:
+    c = np.ascontiguousarray(cost, dtype=np.float64)
+    t = np.ascontiguousarray(idle_time, dtype=np.float64)
+    if c.shape != t.shape or c.ndim != 1:
+        raise ValueError("cost and idle_time must be 1-D and of equal length")
+    order = np.zeros(len(c), dtype=np.int32)
+    _check(_lib.pv_retention_order(c.ctypes.data_as(_f64p), t.ctypes.data_as(_f64p), len(c),
+                                   _i32(order)), "pv_retention_order")
+    return order

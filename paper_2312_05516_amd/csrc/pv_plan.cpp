@@ -7,6 +7,8 @@
 #include "pv_plan.h"
 
 #include <algorithm>
+#include <cmath>
+#include <numeric>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -398,6 +400,32 @@ pv_status pv_plan_check_page_table(const pv_plan *plan, const int32_t *page_tabl
             }
         }
     }
+    return PV_OK;
+}
+
+double pv_cost_model(const int32_t *ctx_points, const double *attn_cost, int32_t n, double c_other,
+                     int32_t l)
+{
+    if (n <= 0) return c_other;
+    if (!ctx_points || !attn_cost) return std::nan("");
+    if (n == 1) return attn_cost[0] + c_other;
+    // segment whose right end is the first profiled point >= l (clamped to the outer segments)
+    const int32_t *hi = std::lower_bound(ctx_points + 1, ctx_points + n - 1, l);
+    const int32_t k = (int32_t)(hi - ctx_points) - 1;
+    const double t = ((double)l - ctx_points[k]) / ((double)ctx_points[k + 1] - ctx_points[k]);
+    return attn_cost[k] + t * (attn_cost[k + 1] - attn_cost[k]) + c_other;
+}
+
+pv_status pv_retention_order(const double *cost, const double *idle_time, int32_t n,
+                             int32_t *order_out)
+{
+    if (n < 0 || (n > 0 && (!cost || !idle_time || !order_out))) return PV_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (!(idle_time[i] > 0.0)) return PV_ERR_INVALID_ARG;
+    std::iota(order_out, order_out + n, 0);
+    std::stable_sort(order_out, order_out + n, [&](int32_t a, int32_t b) {
+        return cost[a] / idle_time[a] < cost[b] / idle_time[b];
+    });
     return PV_OK;
 }
 

@@ -179,3 +179,24 @@ def test_workspace_bound_covers_plans(pv):
                                         int(b.kv_lens.max()))
         assert bound >= pv.plan_workspace_bytes(plan)
         plan.destroy()
+
+
+def test_cost_model_and_retention_order_match_the_oracle(pv, oracle):
+    """Pure host entry points: parity with the oracle is exact for the order, and to rounding for
+    the interpolation."""
+    pts = [32, 64, 128, 256, 512, 1024, 2048]
+    rng = np.random.default_rng(5)
+    ys = np.cumsum(rng.uniform(0.1, 2.0, size=len(pts)))
+    for l in [1, 16, 32, 33, 64, 100, 128, 1000, 1024, 2047, 2048, 5000]:
+        assert np.isclose(pv.cost_model(pts, ys, 0.7, l), oracle.cost(pts, ys, 0.7, l),
+                          rtol=1e-13, atol=0)
+    assert pv.cost_model([], [], 0.7, 5) == 0.7 and pv.cost_model([8], [2.0], 0.5, 99) == 2.5
+    c = rng.uniform(1, 10, size=200)
+    t = rng.uniform(1, 600, size=200)
+    assert np.array_equal(pv.retention_order(c, t), oracle.retention_order(c, t))
+    c[10:20] = c[10]
+    t[10:20] = t[10]  # ties
+    assert np.array_equal(pv.retention_order(c, t), oracle.retention_order(c, t))
+    with pytest.raises(pv.PvError):
+        pv.retention_order([1.0, 2.0], [3.0, 0.0])
+    assert len(pv.retention_order([], [])) == 0
