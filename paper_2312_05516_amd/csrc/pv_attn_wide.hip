@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
     }
     page_ids(2, id0, id1);
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     for (int b = 0; b < nblocks; ++b) {
@@ -224,12 +224,16 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
                 compute_block(smem[b % STAGES], kb0, std::true_type{});
         }
         // block b+1 (issued one iteration ago) must have landed before the barrier publishes it;
-        // this iteration's own copies may stay in flight
+        // this iteration's own copies may stay in flight.  This wavefront's LDS reads of block b
+        // must have returned too: after the barrier the others refill that stage.  The scheduling
+        // barrier keeps the block's last matrix-core instructions (which consume those reads) in
+        // front of the wait, so the wait itself costs nothing.
+        __builtin_amdgcn_sched_barrier(0);
         asm volatile("" ::: "memory");
         if (more)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * PASSES));
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * PASSES, 0));
         else
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     }

@@ -110,8 +110,12 @@ __device__ __forceinline__ void lds_dma16(const void *uniform_base, uint32_t lan
                  : "memory");
 }
 
-// s_waitcnt immediate that waits until at most N vector-memory operations are outstanding and
-// does not wait on the other counters.
-constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+// s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory operations and at most
+// `lgkm` LDS / scalar-memory operations are outstanding (15 = do not wait on LDS); the export
+// counter is not waited on.
+constexpr int waitcnt_imm(int vm, int lgkm)
+{
+    return (vm & 15) | (7 << 4) | ((lgkm & 15) << 8) | ((vm >> 4) << 14);
+}
 
 }  // namespace pv
