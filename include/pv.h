@@ -22,6 +22,8 @@
  *     before anything is launched.  The *contents* of device index arrays are
  *     not checked by the launching calls; pv_plan_check_page_table() checks a
  *     host copy.
+ *   - A plan may be shared by the launches of many layers, but by one host thread at a time (a
+ *     launch updates the plan's timing state and, the first time, uploads it).
  *   - Supported: page_size 16; head_dim 64 or 128; dtype f16 or bf16;
  *     num_q_heads a multiple of num_kv_heads (consecutive query heads
  *     hq = hk*G .. hk*G+G-1 share KV head hk, G = num_q_heads/num_kv_heads).
