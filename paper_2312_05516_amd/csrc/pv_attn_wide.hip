@@ -209,7 +209,11 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
     }
     page_ids(2, id0, id1);
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
+    // the queries (loaded first) and block 0 must be there; block 1 may still be on its way
+    if (nblocks > 1)
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * PASSES, 0));
+    else
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     for (int b = 0; b < nblocks; ++b) {

@@ -361,3 +361,80 @@ def test_long_prefill_from_empty_cache(oracle):
     b = wl.custom([0, 33, 0], [1500, 0, 1], num_q_heads=2, num_kv_heads=1, head_dim=128,
                   dtype="bf16", seed=71)
     check_case(oracle, H.make_case(b, fill="nan"))
+
+
+def _random_batch(rng, idx):
+    hkv = int(rng.choice([1, 2, 3, 5]))
+    g = int(rng.choice([1, 1, 2, 4, 8, 16]))
+    d = int(rng.choice([64, 128]))
+    dt = str(rng.choice(["f16", "bf16"]))
+    r = int(rng.integers(1, 7))
+    ctx = [int(x) for x in rng.choice([0, 1, 15, 16, 17, 31, 32, 33, 100, 255, 256, 600, 1100], size=r)]
+    qn = [int(x) for x in rng.choice([0, 1, 1, 2, 3, 5, 16, 17, 40, 129, 200], size=r)]
+    if sum(qn) == 0:
+        qn[0] = 1
+    return wl.custom(ctx, qn, num_q_heads=hkv * g, num_kv_heads=hkv, head_dim=d, dtype=dt,
+                     seed=1000 + idx, name=f"random{idx}")
+
+
+@pytest.mark.parametrize("idx", range(12))
+def test_random_batches(oracle, idx):
+    """Seeded random mixes of lengths, head groupings, head sizes and dtypes: both attention
+    kernels, masked/unmasked blocks, empty requests, partial pages."""
+    rng = np.random.default_rng(500 + idx)
+    check_case(oracle, H.make_case(_random_batch(rng, idx), fill="nan"))
+
+
+def test_long_contexts_with_split_kv(oracle):
+    """One generation step over 60 K cached tokens (GQA 8:1) and a 64-token prompt over 20 K
+    tokens: few items, so the plan cuts the KV range into many parts for both kernels."""
+    from paper_2312_05516_amd import binding as pv
+    b = wl.custom([60000], [1], num_q_heads=8, num_kv_heads=1, head_dim=128, dtype="bf16", seed=83)
+    desc = pv.pool_desc(b.num_pages, 1, 128, "bf16")
+    plan = pv.plan_create(desc, 8, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    assert pv.plan_num_work_items(plan, 0) > 50 and pv.plan_num_work_items(plan, 2) == 1
+    plan.destroy()
+    check_case(oracle, H.make_case(b, fill="nan"))
+    b = wl.custom([20000], [64], num_q_heads=2, num_kv_heads=1, head_dim=64, dtype="f16", seed=85)
+    desc = pv.pool_desc(b.num_pages, 1, 64, "f16")
+    plan = pv.plan_create(desc, 2, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    assert pv.plan_num_work_items(plan, 1) > 20 and pv.plan_num_work_items(plan, 2) == 1
+    plan.destroy()
+    check_case(oracle, H.make_case(b, fill="nan"))
+
+
+def test_two_plans_on_two_streams(oracle):
+    """Two batches launched back to back on different streams (each with its own plan, workspace
+    and pools) do not disturb each other."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    cases, runs = [], []
+    for seed, shape in ((91, ([700, 33], [1, 150])), (93, ([64, 2000, 5], [40, 1, 3]))):
+        b = wl.custom(*shape, num_q_heads=8, num_kv_heads=2, head_dim=128, dtype="f16", seed=seed)
+        case = H.make_case(b, fill="nan")
+        desc = pv.pool_desc(b.num_pages, 2, 128, "f16")
+        plan = pv.plan_create(desc, 8, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        pv.plan_upload(plan)
+        t = dict(plan=plan, table=torch.from_numpy(b.page_table).cuda(),
+                 q=H.to_dev_bits(case.q, "f16"), kn=H.to_dev_bits(case.k_new, "f16"),
+                 vn=H.to_dev_bits(case.v_new, "f16"), kp=H.to_dev_bits(case.k_pool0, "f16"),
+                 vp=H.to_dev_bits(case.v_pool0, "f16"), stream=torch.cuda.Stream(),
+                 ws=torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8,
+                                device="cuda"))
+        t["out"] = torch.zeros((b.total_q, 8, 128), dtype=t["q"].dtype, device="cuda")
+        cases.append(case)
+        runs.append(t)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        for case, t in zip(cases, runs):
+            with torch.cuda.stream(t["stream"]):
+                pv.kv_append_planned(t["plan"], t["kn"], t["vn"], t["table"], t["kp"], t["vp"])
+                pv.multi_token_paged_attn_planned(t["plan"], t["q"], t["kp"], t["vp"], t["table"],
+                                                  case.batch.scale, t["out"], t["ws"])
+    torch.cuda.synchronize()
+    for case, t in zip(cases, runs):
+        got = H.bits_to_f64(H.from_dev_bits(t["out"]), "f16")
+        want = oracle_out(oracle, case)
+        assert np.abs(got - want).max() <= H.TOL["f16"]
+        assert np.array_equal(H.from_dev_bits(t["kp"]).ravel(), case.k_pool1)
+        t["plan"].destroy()
