@@ -10,7 +10,8 @@
 // blocks (two pages) of the item's KV range round-robin; nothing is shared between them, so K and
 // V go straight from HBM into registers in the lane order the matrix cores consume (the pool
 // stores runs of 8 elements along the contracted dimension, 16 bytes = one lane's operand), with
-// the next block's loads in flight while the current one is processed.  Scores are produced
+// streaming (non-temporal) loads, since every byte is used once, and with the next block's loads in
+// flight while the current one is processed.  Scores are produced
 // transposed, S^T = K Q^T (16 keys x 16 rows per v_mfma_f32_16x16x32), so that every lane owns one
 // query row: the softmax needs no cross-lane traffic beyond two exchanges for the running
 // maximum, and the probabilities are already laid out as the B operand of O^T += V^T P^T.  The

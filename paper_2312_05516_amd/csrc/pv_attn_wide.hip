@@ -16,7 +16,7 @@
 // consecutive bytes (no bank conflicts, no padding, no transposes).  Scores are produced
 // transposed, S^T = K Q^T (v_mfma_f32_32x32x16), so each lane owns one query row (softmax without
 // cross-lane traffic except one exchange for the maximum) and the probabilities are already the B
-// operand of O^T += V^T P^T.  163 VGPRs and 48 KiB of LDS let three workgroups share a CU, whose
+// operand of O^T += V^T P^T.  About 160 VGPRs and 48 KiB of LDS let three workgroups share a CU, whose
 // wavefronts overlap each other's matrix-core, vector-ALU and LDS phases.  One raw s_barrier per
 // block, preceded by a wait that leaves only the newest loads in flight.  Blocks that touch the
 // causal boundary or the end of the sequence take a separate, masked instantiation so the

@@ -67,14 +67,6 @@ __device__ __forceinline__ u32x4 load16(const void *p)
     return *reinterpret_cast<const u32x4 *>(p);
 }
 
-// max of x over the lane pair (l, l ^ 32), without going through LDS
-__device__ __forceinline__ float half_wave_max(float x)
-{
-    const unsigned u = __builtin_bit_cast(unsigned, x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__builtin_bit_cast(float, r[0]), __builtin_bit_cast(float, r[1]));
-}
-
 // 16-byte load with the streaming (non-temporal) hint: for data that is read once
 __device__ __forceinline__ u32x4 load16_stream(const void *p)
 {
@@ -91,7 +83,6 @@ __device__ __forceinline__ int wave_id()
 }
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
-typedef const __attribute__((address_space(1))) void *global_void_ptr;
 
 // Asynchronous 16-byte-per-lane copy from global memory into LDS: lane l of the wavefront writes
 // lds_base + 16*l.  Issued as raw instructions so that the compiler's wait-count insertion does
