@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
         for (int v = 0; v < 16; ++v) o[blk][v] = 0.f;
     float m_run = -INFINITY;  // reference maximum of the RAW scores (before scaling)
     float l_run = 0.f;        // this lane's share of the running sum
+    float mc = 0.f;           // m_run in the exp2 domain (0 while there is no reference yet)
 
     auto compute_block = [&](const unsigned char *sb, int kb0, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
@@ -146,20 +147,26 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
         float mx = s[0];
 #pragma unroll
         for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // lazy rescale: keep the old reference maximum unless the new one exceeds it by more than
-        // 2^kLazyLog2 in the scaled domain (exact, because softmax is shift-invariant; the
-        // probabilities just range up to 2^kLazyLog2 instead of 1)
-        const float m_new =
-            (m_run == -INFINITY || (mx - m_run) * scale_log2e > kLazyLog2) ? mx : m_run;
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha =
-            m_run == -INFINITY ? 0.f : fast_exp2((m_run - m_safe) * scale_log2e);
-        const float mc = m_safe * scale_log2e;
-        m_run = m_new;
-        if (__any(alpha != 1.f)) {
+        // Lazy rescale: the reference maximum of a row only moves when a new score exceeds it by
+        // more than 2^kLazyLog2 in the scaled domain (exact, because softmax is shift-invariant; the
+        // probabilities just range up to 2^kLazyLog2 instead of 1).  Each lane tests the 16 keys it
+        // holds; only when some lane of the wavefront sees such a score (or has no reference yet)
+        // do the two lanes of a row exchange their maxima and the accumulators get rescaled.
+        const bool grow = m_run == -INFINITY || (mx - m_run) * scale_log2e > kLazyLog2;
+        if (__any(grow)) {
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new =
+                (m_run == -INFINITY || (mx - m_run) * scale_log2e > kLazyLog2) ? mx : m_run;
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha =
+                m_run == -INFINITY ? 0.f : fast_exp2((m_run - m_safe) * scale_log2e);
+            mc = m_safe * scale_log2e;
+            m_run = m_new;
+            l_run *= alpha;
+            if (__any(alpha != 1.f)) {
 #pragma unroll
-            for (int blk = 0; blk < NB; ++blk) o[blk] *= alpha;
+                for (int blk = 0; blk < NB; ++blk) o[blk] *= alpha;
+            }
         }
         // page by page: the matrix-core work of page 0 is issued before the exponentials of page 1,
         // so that inside this wavefront the two have something to overlap with
@@ -175,8 +182,8 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
                     p0 = vis[8 * pg + 2 * jj] ? p0 : 0.f;
                     p1 = vis[8 * pg + 2 * jj + 1] ? p1 : 0.f;
                 }
-                psum += p0 + p1;
                 praw[jj] = T::pack2(p0, p1);
+                psum = T::add_pair(praw[jj], psum);  // the sum of what the matrix core will see
             }
             const vec8 pf = as_vec8<T>(praw);
 #pragma unroll
@@ -195,7 +202,7 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
                 o[blk] = T::mfma32(as_vec8<T>(vf), pf, o[blk]);
             }
         }
-        l_run = l_run * alpha + psum;
+        l_run += psum;
     };
 
     // prologue: blocks 0 and 1 on their way, block 0 landed and visible to everyone; the page ids

@@ -36,6 +36,13 @@ struct F16 {
         h2 v = {(_Float16)lo, (_Float16)hi};
         return __builtin_bit_cast(uint32_t, v);
     }
+    // acc + low half + high half of a packed pair, in fp32 (one v_dot2 against (1, 1))
+    static __device__ __forceinline__ float add_pair(uint32_t packed, float acc)
+    {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const h2 ones = {(_Float16)1.f, (_Float16)1.f};
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, packed), ones, acc, false);
+    }
 };
 
 struct BF16 {
@@ -53,6 +60,12 @@ struct BF16 {
         typedef __bf16 b2 __attribute__((ext_vector_type(2)));
         b2 v = {(__bf16)lo, (__bf16)hi};
         return __builtin_bit_cast(uint32_t, v);
+    }
+    static __device__ __forceinline__ float add_pair(uint32_t packed, float acc)
+    {
+        typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+        const b2 ones = {(__bf16)1.f, (__bf16)1.f};
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, packed), ones, acc, false);
     }
 };
 
