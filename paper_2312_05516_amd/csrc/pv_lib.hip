@@ -71,17 +71,6 @@ static pv_status upload(pv_plan *plan)
     plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
     plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
     plan->d_append_groups = reinterpret_cast<AppendGroup *>(b + parts[7].off);
-    if (!plan->narrow.empty() && !plan->wide.empty() && !std::getenv("PV_NO_SIDE_STREAM")) {
-        hipStream_t side;
-        hipEvent_t fork, join;
-        if (hipStreamCreateWithFlags(&side, hipStreamNonBlocking) != hipSuccess ||
-            hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess)
-            return PV_ERR_HIP;
-        plan->side_stream = side;
-        plan->ev_fork = fork;
-        plan->ev_join = join;
-    }
     plan->device = dev;
     plan->uploaded = true;
     return PV_OK;
@@ -161,9 +150,6 @@ void pv_plan_destroy(pv_plan *plan)
     if (plan->d_blob) (void)hipFree(plan->d_blob);
     for (void *e : plan->events)
         if (e) (void)hipEventDestroy(static_cast<hipEvent_t>(e));
-    if (plan->ev_fork) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_fork));
-    if (plan->ev_join) (void)hipEventDestroy(static_cast<hipEvent_t>(plan->ev_join));
-    if (plan->side_stream) (void)hipStreamDestroy(static_cast<hipStream_t>(plan->side_stream));
     delete plan;
 }
 
@@ -205,19 +191,7 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
     pv_status s = pv::ensure_ready(plan);
     if (s != PV_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // A mixed batch has work for both attention kernels; they touch disjoint rows, so the narrow
-    // one runs on the plan's side stream between a fork and a join event (not while per-kernel
-    // timing is on: then the kernels run one after the other so that each duration is its own).
-    const bool fork =
-        plan->side_stream && !plan->timing && !plan->narrow.empty() && !plan->wide.empty();
-    hipStream_t narrow_stream = st;
-    if (fork) {
-        narrow_stream = static_cast<hipStream_t>(plan->side_stream);
-        if (hipEventRecord(static_cast<hipEvent_t>(plan->ev_fork), st) != hipSuccess ||
-            hipStreamWaitEvent(narrow_stream, static_cast<hipEvent_t>(plan->ev_fork), 0) !=
-                hipSuccess)
-            return PV_ERR_HIP;
-    }
+    // the kernels touch disjoint rows of `out`; both run on the caller's stream
     {
         pv::KernelTimer t(plan, 1, st, !plan->wide.empty());
         if (pv::launch_attn_wide(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
@@ -225,14 +199,9 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
             return PV_ERR_HIP;
     }
     {
-        pv::KernelTimer t(plan, 0, narrow_stream, !plan->narrow.empty());
+        pv::KernelTimer t(plan, 0, st, !plan->narrow.empty());
         if (pv::launch_attn_narrow(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
-                                   narrow_stream) != hipSuccess)
-            return PV_ERR_HIP;
-    }
-    if (fork) {
-        if (hipEventRecord(static_cast<hipEvent_t>(plan->ev_join), narrow_stream) != hipSuccess ||
-            hipStreamWaitEvent(st, static_cast<hipEvent_t>(plan->ev_join), 0) != hipSuccess)
+                                   st) != hipSuccess)
             return PV_ERR_HIP;
     }
     {

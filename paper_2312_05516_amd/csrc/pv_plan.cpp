@@ -45,6 +45,7 @@ Tuning default_tuning()
     t.min_split_keys = env_int("PV_MIN_SPLIT_KEYS", 256);
     t.wide_min_rows = env_int("PV_WIDE_MIN_ROWS", 33);
     t.xcds = env_int("PV_XCDS", 8);
+    t.unify = env_int("PV_UNIFY", 1) == 1 ? 1 : 0;  // any other positive value switches it off
     return t;
 }
 
@@ -54,22 +55,29 @@ static int64_t item_cost(const WorkItem &w, int rows_per_step)
     return (int64_t)(w.kv_end - w.kv_begin) * steps;
 }
 
-// Cut long items into parts of the KV range when the list is too short to fill the GPU.
+// Cut long items into parts of the KV range.  With `chunk` = the KV length that would give about
+// split_target equal items (never below min_split_keys):
+//  * a list too short to fill the GPU (fewer than split_target items) is cut everywhere, every
+//    item longer than `chunk` into parts of about that length;
+//  * in a longer list only the outliers are cut, items more than twice as long as `chunk`, because
+//    one workgroup walking such an item alone would outlast everything else.
 static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &combine,
                         int64_t &slots, const Tuning &tune)
 {
-    if (items.empty() || (int64_t)items.size() >= tune.split_target) return;
+    if (items.empty()) return;
     int64_t total_keys = 0;
     for (const WorkItem &w : items) total_keys += w.kv_end - w.kv_begin;
     int64_t chunk = (total_keys + tune.split_target - 1) / tune.split_target;
     chunk = std::max<int64_t>(chunk, tune.min_split_keys);
     chunk = (chunk + kKvBlock - 1) / kKvBlock * kKvBlock;
+    const bool outliers_only = (int64_t)items.size() >= tune.split_target;
     std::vector<WorkItem> result;
     result.reserve(items.size() * 2);
     for (const WorkItem &w : items) {
         const int64_t len = w.kv_end - w.kv_begin;
         int64_t parts = (len + chunk - 1) / chunk;
-        if (parts <= 1 || len < 2 * (int64_t)tune.min_split_keys) {
+        if (parts <= 1 || len < 2 * (int64_t)tune.min_split_keys ||
+            (outliers_only && len <= 2 * chunk)) {
             result.push_back(w);
             continue;
         }
@@ -205,9 +213,6 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     plan->uploaded = false;
     plan->device = -1;
     plan->d_blob = nullptr;
-    plan->side_stream = nullptr;
-    plan->ev_fork = nullptr;
-    plan->ev_join = nullptr;
     plan->timing = false;
     for (void *&e : plan->events) e = nullptr;
     for (bool &u : plan->event_used) u = false;
@@ -233,6 +238,29 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
         }
     }
 
+    // One attention launch instead of two for a mixed batch.  An item of the matrix-core kernel
+    // holds a workgroup slot for one step per 32 keys whatever its row count, so a small unit
+    // (generation step) is cheaper in the bandwidth-oriented kernel; but a second launch has a
+    // fixed cost and the two kernels cannot share a CU.  When the matrix-core items are at least a
+    // fifth of all 32-key steps of the batch, everything goes to that kernel.
+    bool all_wide = false;
+    if (tune.unify) {
+        int64_t wide_steps = 0, small_steps = 0;
+        for (int32_t r = 0; r < num_reqs; ++r) {
+            const int64_t n = q_lens[r], c = ctx_lens[r];
+            if (n == 0) continue;
+            const int64_t rows_total = n * G;
+            if (rows_total >= tune.wide_min_rows) {
+                for (int64_t rb = 0; rb < rows_total; rb += kWideRows) {
+                    const int64_t last = (std::min<int64_t>(rows_total, rb + kWideRows) - 1) / G;
+                    wide_steps += (c + last + 1 + kKvBlock - 1) / kKvBlock;
+                }
+            } else {
+                small_steps += (c + n + kKvBlock - 1) / kKvBlock;
+            }
+        }
+        all_wide = wide_steps > 0 && 4 * wide_steps >= small_steps;
+    }
     for (int32_t r = 0; r < num_reqs; ++r) {
         const int32_t n = q_lens[r], c = ctx_lens[r];
         if (n == 0) continue;
@@ -248,7 +276,7 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
             w.partial_base = -1;
             w.q_row0 = plan->q_start[r];
             w.ctx = c;
-            const bool use_wide = rows_total >= tune.wide_min_rows;
+            const bool use_wide = rows_total >= tune.wide_min_rows || all_wide;
             const int32_t tile = use_wide ? kWideRows : kNarrowRows;
             for (int32_t rb = 0; rb < rows_total; rb += tile) {
                 w.row_begin = rb;
@@ -267,7 +295,7 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
         return PV_ERR_OUT_OF_RANGE;
     }
     order_items(plan->narrow, kNarrowRows, tune.xcds);
-    order_items(plan->wide, 32, tune.xcds);
+    order_items(plan->wide, env_int("PV_WIDE_COST_ROWS", kWideRows), tune.xcds);
     plan->partial_slots = slots;
     for (size_t i = 0; i < plan->combine.size(); ++i)
         for (int32_t r0 = 0; r0 < plan->combine[i].row_count; r0 += 8)

@@ -67,6 +67,8 @@ struct Tuning {
     int32_t wide_min_rows;   // (request, KV head) units with n*G >= this use the matrix-core
                              // kernel; smaller ones are cut into 16-row items of the narrow kernel
     int32_t xcds;            // L2 domains the work list is interleaved over
+    int32_t unify;           // 1: a batch whose matrix-core work is a sizeable share sends its
+                             // small units to that kernel too (one attention launch, not two)
 };
 
 }  // namespace pv
@@ -95,11 +97,6 @@ struct pv_plan {
     pv::CombineItem *d_combine;
     pv::AppendGroup *d_append_groups;
     pv::CombineChunk *d_combine_chunks;
-
-    // second stream (default priority) and fork/join events: the two attention kernels of a mixed
-    // batch are independent and run side by side
-    void *side_stream;
-    void *ev_fork, *ev_join;
 
     // optional per-kernel timing: events[2*kind], events[2*kind+1] bracket kernel `kind`
     bool timing;

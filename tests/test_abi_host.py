@@ -126,6 +126,38 @@ def test_plan_splits_long_single_request(pv):
     plan.destroy()
 
 
+def test_plan_sends_small_units_to_the_matrix_core_kernel_when_prompts_dominate(pv):
+    """A mixed batch is one attention launch when the prompt work is at least a fifth of all 32-key
+    steps, two launches (generation steps in the bandwidth-oriented kernel) otherwise."""
+    desc = pv.pool_desc(4096, 4, 128, "f16")
+    # prompt of 200 tokens over 1000 cached: 2 tiles x 38 steps; generation steps: 2 x 32 steps
+    plan = pv.plan_create(desc, 4, [1000, 1000, 1000], [200, 1, 1], 128)
+    assert pv.plan_num_work_items(plan, 0) == 0
+    rows = sorted(int(it[3]) for it in _items(pv, plan, 1))
+    assert rows[0] == 1 and rows[-1] == 128
+    plan.destroy()
+    # the same prompt next to 40 generation steps over 4000 cached tokens each: 76 vs 5000 steps
+    plan = pv.plan_create(desc, 4, [1000] + [4000] * 40, [200] + [1] * 40, 256)
+    assert pv.plan_num_work_items(plan, 0) > 0 and pv.plan_num_work_items(plan, 1) > 0
+    assert all(int(it[3]) > 32 for it in _items(pv, plan, 1))
+    plan.destroy()
+
+
+def test_plan_cuts_outliers_of_a_long_list(pv):
+    """More than split_target items, one of them far longer than the rest: only that one is cut."""
+    desc = pv.pool_desc(1 << 16, 8, 128, "bf16")
+    ctx = [300] * 200 + [60000]
+    plan = pv.plan_create(desc, 8, ctx, [1] * 201, 4096)
+    items = _items(pv, plan, 0)
+    assert len(items) > 201 * 8
+    for it in items:
+        assert (int(it[7]) > 1) == (int(it[0]) == 200)
+    longest = max(int(it[5] - it[4]) for it in items)
+    assert longest < 60000 // 4
+    assert pv.plan_num_work_items(plan, 2) == 8
+    plan.destroy()
+
+
 def test_plan_rejects_bad_arguments(pv):
     good = pv.pool_desc(64, 4, 64, "f16")
     with pytest.raises(pv.PvError) as e:
