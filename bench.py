@@ -57,9 +57,9 @@ def parse_args():
                     help="launch every step eagerly instead of replaying one captured HIP graph "
                     "per KV pool (the step of a small batch is otherwise bound by host launch time)")
     ap.add_argument("--serial-kernels", action="store_true",
-                    help="run every step in the library's timing mode (the two attention kernels "
-                    "one after the other instead of side by side): for rocprofv3 runs whose "
-                    "per-kernel durations should be each kernel's own")
+                    help="keep the library's per-kernel event timing on in every step and launch "
+                    "eagerly: for rocprofv3 runs whose per-kernel averages are compared with "
+                    "the bench line's kernel_ms")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run plain device-to-device copies of this many GiB (untimed): the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")

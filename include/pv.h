@@ -164,10 +164,8 @@ pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_n
  * are accumulated in fp32; out is rounded to the 16-bit dtype.  Must run after the append of
  * the same batch on the same stream.
  *   q, out     : device [total_q, Hq, D]
- * Launches at most three kernels.  When the batch has work for both attention kernels, the
- * bandwidth-oriented one is launched on a second stream that belongs to the plan (default
- * priority), forked from and joined back into `stream` with events, so for the caller the call
- * still behaves as one asynchronous operation on `stream`.
+ * Launches at most three kernels (matrix-core attention, bandwidth-oriented attention, merge of
+ * split KV ranges), all on `stream`; which of them a batch needs is decided by the plan.
  *   workspace  : device, >= pv_plan_workspace_bytes(plan) bytes, 256-byte aligned; may be NULL
  *                when that is 0.  Its contents are scratch (partial results of split KV
  *                ranges); two launches that overlap in time need different workspaces.
@@ -182,9 +180,6 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
  * records a pair of HIP events around each kernel it launches (on the launch stream; the events
  * belong to the plan).  pv_plan_kernel_ms waits for the end event of that kernel in the plan's most
  * recent launch and returns its duration in milliseconds; *ms = -1 if that kernel did not run.
- * While timing is on, the two attention kernels of a mixed batch run one after the other on the
- * launch stream (normally the bandwidth-oriented one runs concurrently on a second stream owned by
- * the plan), so that every duration is that kernel's own.
  * kind: 0 = bandwidth-oriented attention kernel, 1 = matrix-core attention kernel,
  *       2 = split-KV combine, 3 = KV append.
  */
