@@ -77,6 +77,14 @@ def _bind(lib):
     lib.pvo_cost.argtypes = [i32p, f64p, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
     lib.pvo_retention_order.restype = ctypes.c_int
     lib.pvo_retention_order.argtypes = [f64p, f64p, ctypes.c_int32, i32p]
+    f32p = ctypes.POINTER(ctypes.c_float)
+    lib.pvo_rope_table.restype = ctypes.c_int
+    lib.pvo_rope_table.argtypes = [ctypes.c_double, ctypes.c_int32, ctypes.c_int32, f32p]
+    lib.pvo_rope.restype = ctypes.c_int
+    lib.pvo_rope.argtypes = [u16p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, i32p, f32p,
+                             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, f64p]
+    lib.pvo_round16.restype = ctypes.c_int
+    lib.pvo_round16.argtypes = [f64p, ctypes.c_int64, ctypes.c_int32, u16p]
     lib.pvo_pages_gather.restype = ctypes.c_int
     lib.pvo_pages_gather.argtypes = [dp, u16p, u16p, i32p, ctypes.c_int32, u16p]
     lib.pvo_pages_scatter.restype = ctypes.c_int
@@ -248,3 +256,38 @@ def retention_order(cost_values, idle_time) -> np.ndarray:
     _check(lib.pvo_retention_order(_p(c, ctypes.c_double), _p(t, ctypes.c_double), len(c),
                                    _p(order, ctypes.c_int32)), "retention_order")
     return order
+
+
+ROPE_STYLES = {"interleaved": 0, "half": 1}
+
+
+def rope_table(base: float, head_dim: int, max_pos: int) -> np.ndarray:
+    """float32 [max_pos, head_dim]: D/2 cosines then D/2 sines of t * base^(-2i/D)."""
+    out = np.zeros((max_pos, head_dim), dtype=np.float32)
+    _check(_load().pvo_rope_table(float(base), int(head_dim), int(max_pos),
+                                  _p(out, ctypes.c_float)), "pvo_rope_table")
+    return out
+
+
+def rope(x_bits: np.ndarray, positions, table: np.ndarray, style: str, dtype: str) -> np.ndarray:
+    """Rotary embedding of x [rows, heads, D] (16-bit patterns) at positions [rows]; float64,
+    not rounded."""
+    x = np.ascontiguousarray(x_bits, dtype=np.uint16)
+    rows, heads, D = x.shape
+    pos = _i32(positions)
+    tab = np.ascontiguousarray(table, dtype=np.float32)
+    assert pos.shape == (rows,) and tab.ndim == 2 and tab.shape[1] == D
+    out = np.zeros((rows, heads, D), dtype=np.float64)
+    _check(_load().pvo_rope(_p(x, ctypes.c_uint16), rows, heads, D, _p(pos, ctypes.c_int32),
+                            _p(tab, ctypes.c_float), tab.shape[0], ROPE_STYLES[style],
+                            DTYPES[dtype], _p(out, ctypes.c_double)), "pvo_rope")
+    return out
+
+
+def round16(values: np.ndarray, dtype: str) -> np.ndarray:
+    """Nearest 16-bit value (ties to even) of every float64 in `values`, as bit patterns."""
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    out = np.zeros(v.shape, dtype=np.uint16)
+    _check(_load().pvo_round16(_p(v, ctypes.c_double), v.size, DTYPES[dtype],
+                               _p(out, ctypes.c_uint16)), "pvo_round16")
+    return out

@@ -317,3 +317,94 @@ int pvo_retention_order(const double *cost, const double *idle_time, int32_t n, 
     }
     return PVO_OK;
 }
+
+/*
+ * Rotary position embedding in front of the append: the producer of the new K rows (and of the
+ * Q rows) in the Llama 2 models the paper serves (Section 6.1 names rotary embedding as one of
+ * their features; Section 4.4.1 has the new K/V stored after the linear layers produce them).
+ * The paper does not print the transform; it is the published RoFormer one: the head dimension
+ * is split into D/2 pairs, pair i of a token at logical position t is rotated by the angle
+ * t * theta_i with theta_i = base^(-2i/D).  Two pairings are in use and both are provided:
+ *   style 0 (interleaved): pair i = elements (2i, 2i+1);
+ *   style 1 (half split):  pair i = elements (i, i + D/2).
+ *   out_a = a cos - b sin,   out_b = b cos + a sin.
+ * The angles come from a table the caller passes in (float, [max_pos][D]: D/2 cosines then D/2
+ * sines per position), so that the arithmetic checked here is the rotation itself; the table
+ * generator below is the definition written out in double precision.
+ */
+int pvo_rope_table(double base, int32_t D, int32_t max_pos, float *table)
+{
+    if (!(base > 0.0) || D <= 0 || D % 2 != 0 || max_pos < 0 || !table) return PVO_BAD_ARG;
+    for (int64_t t = 0; t < max_pos; ++t)
+        for (int32_t i = 0; i < D / 2; ++i) {
+            const double theta = pow(base, -2.0 * (double)i / (double)D);
+            table[t * D + i] = (float)cos((double)t * theta);
+            table[t * D + D / 2 + i] = (float)sin((double)t * theta);
+        }
+    return PVO_OK;
+}
+
+/* x: [rows, heads, D] 16-bit; pos: [rows]; out: [rows, heads, D] doubles, not rounded. */
+int pvo_rope(const uint16_t *x, int64_t rows, int32_t heads, int32_t D, const int32_t *pos,
+             const float *table, int32_t max_pos, int32_t style, int32_t dtype, double *out)
+{
+    if (rows < 0 || heads <= 0 || D <= 0 || D % 2 != 0 || (style != 0 && style != 1) ||
+        (dtype != 0 && dtype != 1))
+        return PVO_BAD_ARG;
+    for (int64_t r = 0; r < rows; ++r) {
+        if (pos[r] < 0 || pos[r] >= max_pos) return PVO_BAD_ARG;
+        const float *cs = table + (int64_t)pos[r] * D;
+        for (int32_t h = 0; h < heads; ++h) {
+            const uint16_t *src = x + (r * heads + h) * D;
+            double *dst = out + (r * heads + h) * D;
+            for (int32_t i = 0; i < D / 2; ++i) {
+                const int32_t ia = style == 0 ? 2 * i : i;
+                const int32_t ib = style == 0 ? 2 * i + 1 : i + D / 2;
+                const double a = pvo_widen(src[ia], dtype), b = pvo_widen(src[ib], dtype);
+                const double c = (double)cs[i], s = (double)cs[D / 2 + i];
+                dst[ia] = a * c - b * s;
+                dst[ib] = b * c + a * s;
+            }
+        }
+    }
+    return PVO_OK;
+}
+
+/*
+ * Round a double to the nearest value of a 16-bit format, ties to even (the rounding the
+ * paper's 16-bit storage implies), and return its bit pattern.  p = significand bits including
+ * the hidden one (11 / 8), emin = exponent of the smallest normal (-14 / -126), emax = exponent
+ * of the largest finite value (15 / 127).
+ */
+static uint16_t pvo_round16_one(double v, int dtype)
+{
+    const int p = dtype == 0 ? 11 : 8, emin = dtype == 0 ? -14 : -126, emax = dtype == 0 ? 15 : 127;
+    const int ebits = dtype == 0 ? 5 : 8, bias = dtype == 0 ? 15 : 127;
+    const uint16_t sign = (uint16_t)(signbit(v) ? 0x8000u : 0u);
+    const uint16_t inf = (uint16_t)(((1u << ebits) - 1u) << (p - 1));
+    if (isnan(v)) return (uint16_t)(sign | inf | (1u << (p - 2)));
+    double a = fabs(v);
+    if (isinf(a)) return (uint16_t)(sign | inf);
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e); /* a = f * 2^e, f in [0.5, 1)  ->  floor(log2 a) = e - 1 */
+    int ex = e - 1;
+    if (ex < emin) ex = emin; /* subnormal range shares the quantum of the smallest normal */
+    const double quantum = ldexp(1.0, ex - (p - 1));
+    double n = nearbyint(a / quantum); /* exact division; default rounding mode = ties to even */
+    if (n >= ldexp(1.0, p)) { /* rounded up into the next binade */
+        n /= 2.0;
+        ex += 1;
+    }
+    if (ex > emax) return (uint16_t)(sign | inf);
+    const uint32_t ni = (uint32_t)n;
+    if (ni < (1u << (p - 1))) return (uint16_t)(sign | ni); /* subnormal (ex == emin) */
+    return (uint16_t)(sign | ((uint32_t)(ex + bias) << (p - 1)) | (ni - (1u << (p - 1))));
+}
+
+int pvo_round16(const double *v, int64_t n, int32_t dtype, uint16_t *out)
+{
+    if (n < 0 || (dtype != 0 && dtype != 1)) return PVO_BAD_ARG;
+    for (int64_t i = 0; i < n; ++i) out[i] = pvo_round16_one(v[i], dtype);
+    return PVO_OK;
+}
