@@ -53,6 +53,9 @@ def parse_args():
     ap.add_argument("--swap", action="store_true",
                     help="instead of the step benchmark, time page gather / scatter (tier swapping) "
                     "through device staging and through pinned host memory")
+    ap.add_argument("--rope", action="store_true",
+                    help="time the fused rotary-embedding + KV-append call next to the plain "
+                    "append on the mixed and decode configurations")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every step eagerly instead of replaying one captured HIP graph "
                     "per KV pool (the step of a small batch is otherwise bound by host launch time)")
@@ -486,6 +489,53 @@ def swap_bench(reps: int = 20) -> dict:
     return res
 
 
+def rope_bench(reps: int = 50) -> list:
+    """Fused rotary embedding + KV append (one launch: rotate Q, rotate and store K, store V) next to
+    the plain append, per configuration.  Bytes per call: K, V rows read and written, Q rows read
+    and written, one table row (D floats) per new token."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    res = []
+    for name in ("mha13b", "gqa70b", "decode_heavy"):
+        b = make_batch(name)
+        db = DeviceBatch(b, 2, serial=False, use_graph=False)
+        table = torch.from_numpy(pv.rope_table(10000.0, b.head_dim, int(b.kv_lens.max()))).cuda()
+        q_out = torch.empty_like(db.q)
+
+        def timed(fn):
+            for i in range(5):
+                fn(i)
+            torch.cuda.synchronize()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            ev[0].record()
+            for i in range(reps):
+                fn(i)
+            ev[1].record()
+            torch.cuda.synchronize()
+            return ev[0].elapsed_time(ev[1]) / reps
+
+        L = db.layers
+        t_plain = timed(lambda i: pv.kv_append_planned(db.plan, db.kn, db.vn, db.table,
+                                                       db.kp[i % L], db.vp[i % L]))
+        out = {"workload": name, "new_tokens": int(b.total_q), "append_ms": round(t_plain, 5)}
+        for style in ("interleaved", "half"):
+            t = timed(lambda i: pv.rope_kv_append_planned(db.plan, db.q, q_out, db.kn, db.vn,
+                                                          table, style, db.table, db.kp[i % L],
+                                                          db.vp[i % L]))
+            nbytes = b.total_q * b.head_dim * (2 * 2 * 2 * b.num_kv_heads + 2 * 2 * b.num_q_heads + 4)
+            out[f"rope_append_{style}_ms"] = round(t, 5)
+            out[f"rope_append_{style}_GBps"] = round(nbytes / t / 1e6, 1)
+            out["bytes"] = int(nbytes)
+        best = min(out["rope_append_interleaved_ms"], out["rope_append_half_ms"])
+        out["roofline"] = {"bound": "hbm", "unit": "GB/s", "peak": HBM_PEAK_GBPS,
+                           "achieved": round(out["bytes"] / best / 1e6, 1),
+                           "frac": round(out["bytes"] / best / 1e6 / HBM_PEAK_GBPS, 4),
+                           "kernel": "rope_append_kernel"}
+        res.append(out)
+        db.close()
+    return res
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -507,6 +557,11 @@ def main():
         print(json.dumps({"metric": "attention cost of one 32-token chunk vs context size "
                           "(40 heads, head size 128, fp16)", "unit": "ms", "n_gpus": 1,
                           "data": "synthetic", "cost_profile": cost_profile()}))
+        return
+    if args.rope:
+        print(json.dumps({"metric": "fused rotary embedding + KV append, ms per call "
+                          "(back-to-back calls on one stream)", "unit": "ms", "n_gpus": 1,
+                          "data": "synthetic", "peak_GBps": HBM_PEAK_GBPS, "rope": rope_bench()}))
         return
     if args.swap:
         print(json.dumps({"metric": "page gather/scatter for tier swapping (chunks of two 16-token "

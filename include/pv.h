@@ -230,6 +230,36 @@ pv_status pv_pages_scatter(const pv_pool_desc *pool, const void *staging,
                            void *v_pages, void *stream);
 
 /*
+ * Rotary position embedding fused with the KV append: the producer step in front of the hot path
+ * for the Llama 2 models of the paper (Section 6.1 names rotary embedding among their features;
+ * Section 4.4.1: the linear layers produce Q/K/V, the new K/V are stored, attention follows).
+ * The paper does not print the transform; it is the published RoFormer one.  For request r and
+ * new token j < q_lens[r] at logical position t = ctx_lens[r] + j, pair i of every head (of k_new
+ * and of q_in) is rotated by the angle t * theta_i:
+ *     out_a = a cos - b sin,   out_b = b cos + a sin,
+ *   style 0 (interleaved): (a, b) = elements (2i, 2i+1);  style 1 (half split): (i, i + D/2).
+ * The rotated K rows and the unchanged V rows are stored as by pv_kv_append_planned; the rotated
+ * Q rows go to q_out (may be q_in itself).  Arithmetic in fp32, rounded to the 16-bit type
+ * (nearest even); V is moved bit for bit; slots that are not addressed keep their contents.
+ *   q_in, q_out : device [total_q, Hq, D]; both NULL = K/V only
+ *   k_new, v_new: device [total_q, Hkv, D]
+ *   cos_sin     : device float [max_pos, D]: for position t, D/2 cosines then D/2 sines of
+ *                 t * theta_i (pv_rope_table fills a host copy with theta_i = base^(-2i/D))
+ *   max_pos     : rows of the table; PV_ERR_OUT_OF_RANGE unless every ctx_lens[r] + q_lens[r]
+ *                 <= max_pos
+ * One launch on `stream`, asynchronous, no allocation.
+ */
+pv_status pv_rope_kv_append_planned(pv_plan *plan, const void *q_in, void *q_out,
+                                    const void *k_new, const void *v_new, const float *cos_sin,
+                                    int32_t max_pos, int32_t style, const int32_t *page_table,
+                                    void *k_pages, void *v_pages, void *stream);
+
+/* Host: table[t*D + i] = cos(t * base^(-2i/D)), table[t*D + D/2 + i] = sin(same), t < max_pos,
+ * i < D/2, evaluated in double precision and rounded to float.  PV_ERR_INVALID_ARG unless
+ * base > 0, head_dim is even and positive, max_pos >= 0 and table is not NULL. */
+pv_status pv_rope_table(double base, int32_t head_dim, int32_t max_pos, float *table /* host */);
+
+/*
  * Recomputation-cost model of the eviction policy (paper Section 4.3.1).  Pure host code.
  * Cost(l) = Cost_attention(l) + c_other is the cost of recomputing one 32-token chunk whose
  * attention spans l context tokens; Cost_attention is profiled at a few context sizes (the paper

@@ -35,6 +35,7 @@ EXPORTS = [
     "pv_kv_append_planned", "pv_multi_token_paged_attn_planned",
     "pv_kv_append", "pv_multi_token_paged_attn", "pv_attn_workspace_bytes",
     "pv_pages_gather", "pv_pages_scatter", "pv_cost_model", "pv_retention_order",
+    "pv_rope_kv_append_planned", "pv_rope_table",
 ]
 
 
@@ -113,6 +114,11 @@ _lib.pv_cost_model.restype = ctypes.c_double
 _lib.pv_cost_model.argtypes = [_i32p, _f64p, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
 _lib.pv_retention_order.restype = ctypes.c_int
 _lib.pv_retention_order.argtypes = [_f64p, _f64p, ctypes.c_int32, _i32p]
+_lib.pv_rope_kv_append_planned.restype = ctypes.c_int
+_lib.pv_rope_kv_append_planned.argtypes = [_vp] * 6 + [ctypes.c_int32, ctypes.c_int32] + [_vp] * 4
+_lib.pv_rope_table.restype = ctypes.c_int
+_lib.pv_rope_table.argtypes = [ctypes.c_double, ctypes.c_int32, ctypes.c_int32,
+                               ctypes.POINTER(ctypes.c_float)]
 _lib.pv_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.pv_attn_workspace_bytes.argtypes = [_descp] + [ctypes.c_int32] * 4
 
@@ -279,6 +285,27 @@ def kv_append_planned(plan: Plan, k_new, v_new, page_table, k_pages, v_pages, st
     _check(_lib.pv_kv_append_planned(plan.handle, _ptr(k_new), _ptr(v_new), _ptr(page_table),
                                      _ptr(k_pages), _ptr(v_pages), _stream(stream)),
            "pv_kv_append_planned")
+
+
+ROPE_STYLES = {"interleaved": 0, "half": 1}
+
+
+def rope_table(base: float, head_dim: int, max_pos: int) -> np.ndarray:
+    """Host float32 [max_pos, head_dim]: D/2 cosines then D/2 sines per position."""
+    out = np.zeros((int(max_pos), int(head_dim)), dtype=np.float32)
+    _check(_lib.pv_rope_table(float(base), int(head_dim), int(max_pos),
+                              out.ctypes.data_as(ctypes.POINTER(ctypes.c_float))), "pv_rope_table")
+    return out
+
+
+def rope_kv_append_planned(plan: Plan, q_in, q_out, k_new, v_new, cos_sin, style, page_table,
+                           k_pages, v_pages, stream=None):
+    """cos_sin: device float32 [max_pos, D] (contiguous); style: "interleaved" | "half" | 0 | 1."""
+    st = ROPE_STYLES[style] if isinstance(style, str) else int(style)
+    _check(_lib.pv_rope_kv_append_planned(plan.handle, _ptr(q_in), _ptr(q_out), _ptr(k_new),
+                                          _ptr(v_new), _ptr(cos_sin), int(cos_sin.shape[0]), st,
+                                          _ptr(page_table), _ptr(k_pages), _ptr(v_pages),
+                                          _stream(stream)), "pv_rope_kv_append_planned")
 
 
 def multi_token_paged_attn_planned(plan: Plan, q, k_pages, v_pages, page_table, scale: float, out,

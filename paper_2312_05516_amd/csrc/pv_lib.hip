@@ -21,6 +21,10 @@ hipError_t launch_attn_wide(const pv_plan *plan, const void *q, const void *k_pa
 hipError_t launch_attn_combine(const pv_plan *plan, const float *ws_o, const float *ws_ml,
                                void *out, hipStream_t stream);
 
+hipError_t launch_rope_append(const pv_plan *plan, int style, const void *q_in, void *q_out,
+                              const void *k_new, const void *v_new, const float *cos_sin,
+                              const int32_t *page_table, void *k_pages, void *v_pages,
+                              hipStream_t stream);
 hipError_t launch_pages_copy(bool gather, const pv_pool_desc *pool, const int32_t *page_ids,
                              int32_t n, void *k_pages, void *v_pages, void *staging,
                              hipStream_t stream);
@@ -167,6 +171,32 @@ pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_n
     {
         pv::KernelTimer t(plan, 3, st, true);
         e = pv::launch_kv_append(plan, k_new, v_new, page_table, k_pages, v_pages, st);
+    }
+    return e == hipSuccess ? PV_OK : PV_ERR_HIP;
+}
+
+pv_status pv_rope_kv_append_planned(pv_plan *plan, const void *q_in, void *q_out,
+                                    const void *k_new, const void *v_new, const float *cos_sin,
+                                    int32_t max_pos, int32_t style, const int32_t *page_table,
+                                    void *k_pages, void *v_pages, void *stream)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (style != 0 && style != 1) return PV_ERR_INVALID_ARG;
+    if ((q_in == nullptr) != (q_out == nullptr)) return PV_ERR_INVALID_ARG;
+    if (plan->total_q == 0) return PV_OK;
+    if (!k_new || !v_new || !cos_sin || !page_table || !k_pages || !v_pages)
+        return PV_ERR_INVALID_ARG;
+    for (int32_t r = 0; r < plan->num_reqs; ++r)
+        if (plan->q_lens[r] > 0 && (int64_t)plan->ctx_lens[r] + plan->q_lens[r] > max_pos)
+            return PV_ERR_OUT_OF_RANGE;
+    pv_status s = pv::ensure_ready(plan);
+    if (s != PV_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    {
+        pv::KernelTimer t(plan, 3, st, true);
+        e = pv::launch_rope_append(plan, style, q_in, q_out, k_new, v_new, cos_sin, page_table,
+                                   k_pages, v_pages, st);
     }
     return e == hipSuccess ? PV_OK : PV_ERR_HIP;
 }

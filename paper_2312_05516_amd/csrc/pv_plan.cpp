@@ -431,6 +431,24 @@ pv_status pv_plan_check_page_table(const pv_plan *plan, const int32_t *page_tabl
     return PV_OK;
 }
 
+pv_status pv_rope_table(double base, int32_t head_dim, int32_t max_pos, float *table)
+{
+    if (!(base > 0.0) || head_dim <= 0 || head_dim % 2 != 0 || max_pos < 0 || !table)
+        return PV_ERR_INVALID_ARG;
+    const int32_t half = head_dim / 2;
+    std::vector<double> theta((size_t)half);
+    for (int32_t i = 0; i < half; ++i) theta[(size_t)i] = std::pow(base, -2.0 * i / head_dim);
+    for (int64_t t = 0; t < max_pos; ++t) {
+        float *row = table + t * head_dim;
+        for (int32_t i = 0; i < half; ++i) {
+            const double angle = (double)t * theta[(size_t)i];
+            row[i] = (float)std::cos(angle);
+            row[half + i] = (float)std::sin(angle);
+        }
+    }
+    return PV_OK;
+}
+
 double pv_cost_model(const int32_t *ctx_points, const double *attn_cost, int32_t n, double c_other,
                      int32_t l)
 {

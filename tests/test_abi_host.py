@@ -158,6 +158,21 @@ def test_plan_cuts_outliers_of_a_long_list(pv):
     plan.destroy()
 
 
+def test_rope_table_matches_the_definition(pv, oracle):
+    """The library's host table generator against the oracle's (independent code, same formula):
+    equal up to one unit in the last place of a float."""
+    for base, D, n in [(10000.0, 128, 300), (500000.0, 64, 77)]:
+        got = pv.rope_table(base, D, n)
+        want = oracle.rope_table(base, D, n)
+        assert got.shape == (n, D)
+        assert np.abs(got.view(np.int32).astype(np.int64) - want.view(np.int32)).max() <= 1
+    assert pv.rope_table(10000.0, 64, 0).shape == (0, 64)
+    for bad in [(0.0, 64, 4), (-2.0, 64, 4), (10000.0, 63, 4)]:
+        with pytest.raises(pv.PvError) as e:
+            pv.rope_table(*bad)
+        assert e.value.status == 1
+
+
 def test_plan_rejects_bad_arguments(pv):
     good = pv.pool_desc(64, 4, 64, "f16")
     with pytest.raises(pv.PvError) as e:

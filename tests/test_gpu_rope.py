@@ -1,0 +1,210 @@
+"""GPU parity of the fused rotary-embedding + KV-append call (C ABI) against the oracle's rotary
+step followed by the oracle's append.  The rotation is floating point rounded to 16 bits: the
+kernel works in fp32, the oracle in fp64, so an element may land on the neighbouring 16-bit value
+when the exact result sits next to a rounding boundary (allowed for at most 0.5 % of the elements,
+within the bound stated at _close_bits); V and every slot that is not addressed are bit-exact."""
+import numpy as np
+import pytest
+
+import helpers as H
+from paper_2312_05516_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def _ulp16(values: np.ndarray, dtype: str) -> np.ndarray:
+    """Spacing of the 16-bit format at |values| (float64 in, float64 out)."""
+    p, emin = (11, -14) if dtype == "f16" else (8, -126)
+    _, e = np.frexp(np.abs(values))                 # |v| = f * 2^e, f in [0.5, 1)
+    ex = np.maximum(e - 1, emin)
+    return np.ldexp(1.0, ex - (p - 1))
+
+
+def _close_bits(got: np.ndarray, want: np.ndarray, what: str, x_in: np.ndarray, dtype: str):
+    """got / want: bit patterns of rotated rows [rows, heads, D]; x_in: the rows before rotation.
+    Bound (derived from the arithmetic): the kernel evaluates a*cos - b*sin in fp32, at most
+    3 * 2^-24 * (|a| + |b|) away from the exact value, and rounds once to 16 bits; the oracle rounds
+    the exact value.  So |got - want| <= ulp16 + 2^-21 * max|x| of the row; and all but a small
+    fraction of the elements are bit-identical."""
+    g, w = H.bits_to_f64(got, dtype), H.bits_to_f64(want, dtype)
+    xmax = np.abs(H.bits_to_f64(x_in, dtype)).max(axis=-1, keepdims=True)
+    bound = _ulp16(w, dtype) + 2.0 ** -21 * xmax
+    bad = np.abs(g - w) > bound
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements outside the rounding bound"
+    assert (got != want).mean() <= 0.005, f"{what}: {(got != want).mean():.4f} of the elements differ"
+
+
+def _pool_rows(b, pool: np.ndarray, oracle) -> np.ndarray:
+    """The new tokens' K rows read back from a pool image: [N, Hkv, D] bit patterns."""
+    out = np.zeros((b.total_q, b.num_kv_heads, b.head_dim), dtype=np.uint16)
+    P, D = b.page_size, b.head_dim
+    d = np.arange(D)
+    for r in range(b.num_reqs):
+        for j in range(int(b.q_lens[r])):
+            t = int(b.ctx_lens[r]) + j
+            page = int(b.page_table[r, t // P])
+            for h in range(b.num_kv_heads):
+                base = ((page * b.num_kv_heads + h) * (D // 8)) * P * 8
+                out[int(b.q_start[r]) + j, h] = pool[base + (d // 8) * P * 8 + (t % P) * 8 + d % 8]
+    return out
+
+
+def _check_k(b, kp_got, kp_want, case, oracle, dtype):
+    """K pool: slots the append does not address are bit-identical to the pool before; the new
+    rows are within the rounding bound of the oracle's."""
+    written = np.zeros(kp_want.size, dtype=bool)
+    P, D = b.page_size, b.head_dim
+    d = np.arange(D)
+    for r in range(b.num_reqs):
+        for t in range(int(b.ctx_lens[r]), int(b.kv_lens[r])):
+            page = int(b.page_table[r, t // P])
+            for h in range(b.num_kv_heads):
+                base = ((page * b.num_kv_heads + h) * (D // 8)) * P * 8
+                written[base + (d // 8) * P * 8 + (t % P) * 8 + d % 8] = True
+    assert np.array_equal(kp_got[~written], case.k_pool0[~written])
+    _close_bits(_pool_rows(b, kp_got, oracle), _pool_rows(b, kp_want, oracle), "K rows", case.k_new,
+                dtype)
+
+
+def _positions(b) -> np.ndarray:
+    pos = np.zeros(b.total_q, dtype=np.int32)
+    for r in range(b.num_reqs):
+        s, n = int(b.q_start[r]), int(b.q_lens[r])
+        pos[s:s + n] = int(b.ctx_lens[r]) + np.arange(n)
+    return pos
+
+
+def _oracle_fused(oracle, case, table, style):
+    """(q rotated bits, K pool after, V pool after) by the oracle: rope -> round -> append."""
+    b = case.batch
+    pos = _positions(b)
+    q_rot = oracle.round16(oracle.rope(case.q, pos, table, style, b.dtype), b.dtype)
+    k_rot = oracle.round16(oracle.rope(case.k_new, pos, table, style, b.dtype), b.dtype)
+    kp, vp = case.k_pool0.copy(), case.v_pool0.copy()
+    oracle.kv_append(H.pool_tuple(b), k_rot, case.v_new, b.page_table, b.ctx_lens, b.q_lens,
+                     b.q_start, kp, vp)
+    return q_rot, k_rot, kp, vp
+
+
+def _gpu_fused(case, table, style, with_q=True, in_place=False, attend=False):
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    b = case.batch
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    kp, vp = H.to_dev_bits(case.k_pool0, b.dtype), H.to_dev_bits(case.v_pool0, b.dtype)
+    tab = torch.from_numpy(table).cuda()
+    pt = torch.from_numpy(b.page_table).cuda()
+    q = H.to_dev_bits(case.q, b.dtype)
+    q_out = q if in_place else torch.zeros_like(q)
+    kn, vn = H.to_dev_bits(case.k_new, b.dtype), H.to_dev_bits(case.v_new, b.dtype)
+    pv.rope_kv_append_planned(plan, q if with_q else None, q_out if with_q else None, kn, vn, tab,
+                              style, pt, kp, vp)
+    out = None
+    if attend:
+        ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
+        out = torch.zeros_like(q)
+        pv.multi_token_paged_attn_planned(plan, q_out, kp, vp, pt, b.scale, out, ws)
+    torch.cuda.synchronize()
+    # the inputs must not have been touched
+    assert np.array_equal(H.from_dev_bits(kn), case.k_new)
+    if not in_place:
+        assert np.array_equal(H.from_dev_bits(q), case.q)
+    res = (H.from_dev_bits(q_out), H.from_dev_bits(kp).ravel(), H.from_dev_bits(vp).ravel(),
+           None if out is None else H.from_dev_bits(out))
+    plan.destroy()
+    return res
+
+
+@pytest.mark.parametrize("style", ["interleaved", "half"])
+@pytest.mark.parametrize("dtype,D", [("f16", 128), ("bf16", 128), ("f16", 64), ("bf16", 64)])
+def test_fused_rope_append_matches_oracle(oracle, style, dtype, D):
+    # full and partial 8-slot groups, a request that starts mid-page, GQA, an empty request
+    b = wl.custom([37, 0, 250, 8, 1000], [5, 33, 1, 0, 19], num_q_heads=6, num_kv_heads=3,
+                  head_dim=D, dtype=dtype, seed=301)
+    case = H.make_case(b, fill="nan")
+    table = oracle.rope_table(10000.0, D, 1100)
+    q_want, _, kp_want, vp_want = _oracle_fused(oracle, case, table, style)
+    q_got, kp_got, vp_got, _ = _gpu_fused(case, table, style)
+    assert np.array_equal(vp_got, vp_want)                      # V: bit-exact everywhere
+    _check_k(b, kp_got, kp_want, case, oracle, dtype)
+    _close_bits(q_got, q_want, "rotated Q", case.q, dtype)
+
+
+def test_slots_not_addressed_keep_their_contents(oracle):
+    b = wl.custom([3, 20], [2, 9], num_q_heads=2, num_kv_heads=2, head_dim=64, dtype="f16", seed=302)
+    case = H.make_case(b, fill="random")
+    table = oracle.rope_table(10000.0, 64, 64)
+    _, _, kp_want, vp_want = _oracle_fused(oracle, case, table, "half")
+    _, kp_got, vp_got, _ = _gpu_fused(case, table, "half")
+    _check_k(b, kp_got, kp_want, case, oracle, b.dtype)
+    assert np.array_equal(vp_got, vp_want)
+
+
+def test_kv_only_and_in_place_queries(oracle):
+    b = wl.custom([100, 7], [40, 1], num_q_heads=8, num_kv_heads=2, head_dim=128, dtype="bf16",
+                  seed=303)
+    case = H.make_case(b, fill="nan")
+    table = oracle.rope_table(10000.0, 128, 160)
+    q_want, _, kp_want, vp_want = _oracle_fused(oracle, case, table, "interleaved")
+    q_got, kp_got, vp_got, _ = _gpu_fused(case, table, "interleaved", with_q=False)
+    assert np.array_equal(q_got, np.zeros_like(q_got))          # q_out was not written
+    _check_k(b, kp_got, kp_want, case, oracle, b.dtype)
+    assert np.array_equal(vp_got, vp_want)
+    q_got, kp_got, _, _ = _gpu_fused(case, table, "interleaved", in_place=True)
+    _close_bits(q_got, q_want, "rotated Q in place", case.q, b.dtype)
+    _check_k(b, kp_got, kp_want, case, oracle, b.dtype)
+
+
+def test_attention_on_rotated_rows(oracle):
+    """The fused call feeds the attention: rotated Q against a history whose K rows were rotated
+    and stored by earlier calls (here: by the oracle) plus the new rotated rows."""
+    b = wl.custom([300, 0, 45], [17, 130, 1], num_q_heads=8, num_kv_heads=2, head_dim=128,
+                  dtype="f16", seed=304)
+    base_case = H.make_case(b, fill="nan")
+    table = oracle.rope_table(10000.0, 128, 400)
+    # history: rotate every past K row at its own position (oracle), then lay the pools out again
+    k_full = []
+    for r in range(b.num_reqs):
+        L = int(b.kv_lens[r])
+        rot = oracle.round16(oracle.rope(base_case.k_full[r], np.arange(L, dtype=np.int32), table,
+                                         "half", b.dtype), b.dtype)
+        c = int(b.ctx_lens[r])
+        mixed = base_case.k_full[r].copy()
+        mixed[:c] = rot[:c]           # past rows are stored rotated; new rows arrive unrotated
+        k_full.append(mixed)
+    case = H.make_case(b, fill="nan", k_full=k_full, v_full=base_case.v_full, q=base_case.q)
+    q_want, _, kp_want, vp_want = _oracle_fused(oracle, case, table, "half")
+    want, _ = oracle.attn(H.pool_tuple(b), b.num_q_heads, q_want, kp_want, vp_want, b.page_table,
+                          b.ctx_lens, b.q_lens, b.q_start, b.scale)
+    _, _, _, out = _gpu_fused(case, table, "half", attend=True)
+    assert np.abs(H.bits_to_f64(out, b.dtype) - want).max() <= H.TOL[b.dtype]
+
+
+def test_bad_arguments_are_rejected(oracle):
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    b = wl.custom([10], [4], num_q_heads=2, num_kv_heads=2, head_dim=64, dtype="f16", seed=305)
+    case = H.make_case(b, fill="zero")
+    desc = pv.pool_desc(b.num_pages, 2, 64, "f16")
+    plan = pv.plan_create(desc, 2, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    kp, vp = H.to_dev_bits(case.k_pool0, "f16"), H.to_dev_bits(case.v_pool0, "f16")
+    q = H.to_dev_bits(case.q, "f16")
+    kn, vn = H.to_dev_bits(case.k_new, "f16"), H.to_dev_bits(case.v_new, "f16")
+    pt = torch.from_numpy(b.page_table).cuda()
+    short = torch.from_numpy(oracle.rope_table(10000.0, 64, 13)).cuda()   # needs 14 positions
+    with pytest.raises(pv.PvError) as e:
+        pv.rope_kv_append_planned(plan, q, q, kn, vn, short, "half", pt, kp, vp)
+    assert e.value.status == 3
+    ok = torch.from_numpy(oracle.rope_table(10000.0, 64, 14)).cuda()
+    with pytest.raises(pv.PvError) as e:
+        pv.rope_kv_append_planned(plan, q, q, kn, vn, ok, 2, pt, kp, vp)
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:
+        pv.rope_kv_append_planned(plan, q, None, kn, vn, ok, 0, pt, kp, vp)
+    assert e.value.status == 1
+    torch.cuda.synchronize()
+    assert np.array_equal(H.from_dev_bits(kp).ravel(), case.k_pool0)   # nothing was launched
+    pv.rope_kv_append_planned(plan, q, q, kn, vn, ok, 0, pt, kp, vp)
+    torch.cuda.synchronize()
+    plan.destroy()
