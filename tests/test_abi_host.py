@@ -226,6 +226,23 @@ def test_workspace_bound_covers_plans(pv):
                                         int(b.kv_lens.max()))
         assert bound >= pv.plan_workspace_bytes(plan)
         plan.destroy()
+    # shapes that make the plan split: one long request alone, an outlier in a long list, a
+    # mixed batch routed to one kernel, seeded random mixes
+    rng = np.random.default_rng(23)
+    shapes = [([50000], [1], 64, 8), ([300] * 200 + [60000], [1] * 201, 8, 8),
+              ([40000, 100, 7000], [200, 1, 1], 8, 2), ([20000], [64], 2, 1)]
+    for _ in range(20):
+        n = int(rng.integers(1, 40))
+        shapes.append((rng.integers(0, 30000, n).tolist(),
+                       rng.choice([0, 1, 1, 1, 5, 40, 300], n).tolist(),
+                       int(rng.choice([8, 16])), int(rng.choice([1, 2, 8]))))
+    for ctx, qn, hq, hkv in shapes:
+        desc = pv.pool_desc(1 << 16, hkv, 128, "bf16")
+        plan = pv.plan_create(desc, hq, ctx, qn, 4096)
+        kv_max = max([c + q for c, q in zip(ctx, qn)] + [0])
+        bound = pv.attn_workspace_bytes(desc, hq, len(ctx), int(sum(qn)), kv_max)
+        assert bound >= pv.plan_workspace_bytes(plan), (ctx[:4], qn[:4], hq, hkv)
+        plan.destroy()
 
 
 def test_cost_model_and_retention_order_match_the_oracle(pv, oracle):
