@@ -413,6 +413,23 @@ def test_long_contexts_with_split_kv(oracle):
     check_case(oracle, H.make_case(b, fill="nan"))
 
 
+def test_outlier_in_a_long_work_list_is_split(oracle):
+    """More than 1024 items, one of them forty times longer than the rest: the plan cuts only that
+    one (both kernels: a batch of generation steps, and a mixed batch in one launch)."""
+    from paper_2312_05516_amd import binding as pv
+    ctx = [40 + 3 * i for i in range(135)] + [9000]
+    for qn, kinds, merges in (([1] * 136, (0,), 8), ([1] * 135 + [200], (1,), 16)):
+        b = wl.custom(ctx, qn, num_q_heads=8, num_kv_heads=8, head_dim=64, dtype="f16", seed=87)
+        desc = pv.pool_desc(b.num_pages, 8, 64, "f16")
+        plan = pv.plan_create(desc, 8, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        for kind in (0, 1):
+            n = pv.plan_num_work_items(plan, kind)
+            assert (n > 1024) == (kind in kinds), (kind, n)
+        assert pv.plan_num_work_items(plan, 2) == merges  # the long request's items only
+        plan.destroy()
+        check_case(oracle, H.make_case(b, fill="nan"))
+
+
 def test_two_plans_on_two_streams(oracle):
     """Two batches launched back to back on different streams (each with its own plan, workspace
     and pools) do not disturb each other."""
