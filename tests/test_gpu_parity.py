@@ -387,7 +387,7 @@ def _random_batch(rng, idx):
                      seed=1000 + idx, name=f"random{idx}")
 
 
-@pytest.mark.parametrize("idx", range(12))
+@pytest.mark.parametrize("idx", range(24))
 def test_random_batches(oracle, idx):
     """Seeded random mixes of lengths, head groupings, head sizes and dtypes: both attention
     kernels, masked/unmasked blocks, empty requests, partial pages."""
