@@ -71,6 +71,14 @@ static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &
     chunk = std::max<int64_t>(chunk, tune.min_split_keys);
     chunk = (chunk + kKvBlock - 1) / kKvBlock * kKvBlock;
     const bool outliers_only = (int64_t)items.size() >= tune.split_target;
+    auto wants_split = [&](const WorkItem &w) {
+        const int64_t len = w.kv_end - w.kv_begin;
+        return len > chunk && len >= 2 * (int64_t)tune.min_split_keys &&
+               !(outliers_only && len <= 2 * chunk);
+    };
+    bool any = false;
+    for (const WorkItem &w : items) any = any || wants_split(w);
+    if (!any) return;  // the common case of a long list: nothing is copied
     std::vector<WorkItem> result;
     result.reserve(items.size() * 2);
     for (const WorkItem &w : items) {
@@ -122,23 +130,39 @@ static void order_items(std::vector<WorkItem> &items, int rows_per_step, int xcd
 {
     if (items.empty()) return;
     if (xcds < 1) xcds = 1;
-    // 1. group by (req, kv_head, split_index); items of a group keep their row order
-    std::stable_sort(items.begin(), items.end(), [](const WorkItem &a, const WorkItem &b) {
+    const size_t n = items.size();
+    // 1. group by (req, kv_head, split_index); items of a group keep their row order.  Sorted as
+    //    (key, position) pairs: the 48-byte items themselves are moved only once, at the end.
+    struct Keyed {
+        int32_t req, kv_head, split_index;
+        uint32_t pos;
+        bool same_group(const Keyed &o) const
+        {
+            return req == o.req && kv_head == o.kv_head && split_index == o.split_index;
+        }
+    };
+    std::vector<Keyed> keyed(n);
+    for (size_t i = 0; i < n; ++i)
+        keyed[i] = Keyed{items[i].req, items[i].kv_head, items[i].split_index, (uint32_t)i};
+    auto before = [](const Keyed &a, const Keyed &b) {
         if (a.req != b.req) return a.req < b.req;
         if (a.kv_head != b.kv_head) return a.kv_head < b.kv_head;
-        return a.split_index < b.split_index;
-    });
-    struct Group { size_t begin, end; int64_t cost; };
+        if (a.split_index != b.split_index) return a.split_index < b.split_index;
+        return a.pos < b.pos;
+    };
+    if (!std::is_sorted(keyed.begin(), keyed.end(), before))
+        std::sort(keyed.begin(), keyed.end(), before);
+    struct Group { uint32_t begin, end; int64_t cost; };
     std::vector<Group> groups;
-    for (size_t i = 0; i < items.size();) {
+    groups.reserve(n);
+    for (size_t i = 0; i < n;) {
         size_t j = i;
         int64_t cost = 0;
-        while (j < items.size() && items[j].req == items[i].req &&
-               items[j].kv_head == items[i].kv_head && items[j].split_index == items[i].split_index) {
-            cost += item_cost(items[j], rows_per_step);
+        while (j < n && keyed[j].same_group(keyed[i])) {
+            cost += item_cost(items[keyed[j].pos], rows_per_step);
             ++j;
         }
-        groups.push_back(Group{i, j, cost});
+        groups.push_back(Group{(uint32_t)i, (uint32_t)j, cost});
         i = j;
     }
     // 2. longest group first (per item, so that a long single item is not hidden behind a group of
@@ -146,26 +170,27 @@ static void order_items(std::vector<WorkItem> &items, int rows_per_step, int xcd
     std::stable_sort(groups.begin(), groups.end(), [&](const Group &a, const Group &b) {
         return a.cost * (int64_t)(b.end - b.begin) > b.cost * (int64_t)(a.end - a.begin);
     });
-    std::vector<std::vector<WorkItem>> queue((size_t)xcds);
+    std::vector<std::vector<uint32_t>> queue((size_t)xcds);
+    for (auto &qv : queue) qv.reserve(n / (size_t)xcds + 16);
     std::vector<int64_t> load((size_t)xcds, 0);
     for (const Group &g : groups) {
         size_t best = 0;
         for (size_t x = 1; x < (size_t)xcds; ++x)
             if (load[x] < load[best]) best = x;
-        for (size_t i = g.begin; i < g.end; ++i) queue[best].push_back(items[i]);
+        for (uint32_t i = g.begin; i < g.end; ++i) queue[best].push_back(keyed[i].pos);
         load[best] += g.cost;
     }
     // 3. interleave: position k*xcds + x takes the k-th item of XCD x's queue; once a queue is
     //    empty its positions are filled from the queues that still have items
     std::vector<WorkItem> out;
-    out.reserve(items.size());
+    out.reserve(n);
     std::vector<size_t> at((size_t)xcds, 0);
     size_t x = 0;
-    while (out.size() < items.size()) {
+    while (out.size() < n) {
         size_t pick = x;
         for (int tries = 0; tries < xcds && at[pick] >= queue[pick].size(); ++tries)
             pick = (pick + 1) % (size_t)xcds;
-        out.push_back(queue[pick][at[pick]++]);
+        out.push_back(items[queue[pick][at[pick]++]]);
         x = (x + 1) % (size_t)xcds;
     }
     items.swap(out);
@@ -260,6 +285,20 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
             }
         }
         all_wide = wide_steps > 0 && 4 * wide_steps >= small_steps;
+    }
+    {
+        // capacity for the item lists, so that filling them does not reallocate
+        size_t n_narrow = 0, n_wide = 0;
+        for (int32_t r = 0; r < num_reqs; ++r) {
+            const int64_t rows_total = (int64_t)q_lens[r] * G;
+            if (rows_total == 0) continue;
+            const bool big = rows_total >= tune.wide_min_rows;
+            const size_t tiles = (size_t)((rows_total + (big ? kWideRows : kNarrowRows) - 1) /
+                                          (big ? kWideRows : kNarrowRows));
+            (big || all_wide ? n_wide : n_narrow) += tiles * (size_t)pool->num_kv_heads;
+        }
+        plan->narrow.reserve(n_narrow);
+        plan->wide.reserve(n_wide);
     }
     for (int32_t r = 0; r < num_reqs; ++r) {
         const int32_t n = q_lens[r], c = ctx_lens[r];
