@@ -131,9 +131,9 @@ size_t pv_plan_workspace_bytes(const pv_plan *plan);
  *   req, kv_head, row_begin, row_count, kv_begin, kv_end, split_index, split_count
  * where a "row" is a (new token, query head of the group) pair, row = token*G + g.  Which kernel
  * a (request, KV head) unit goes to is the plan's decision: more than 32 rows always means the
- * matrix-core kernel (items of at most 128 rows); smaller units join it when the batch's prompt
- * work is at least a fifth of all its 32-key steps (one attention launch instead of two),
- * otherwise they are cut into items of the bandwidth-oriented kernel. */
+ * matrix-core kernel (items of at most 128 rows); smaller units join it when the batch has such
+ * work and the small units are not a large amount of work themselves (one attention launch
+ * instead of two), otherwise they are cut into items of the bandwidth-oriented kernel. */
 int32_t pv_plan_num_work_items(const pv_plan *plan, int32_t kind);
 pv_status pv_plan_work_item(const pv_plan *plan, int32_t kind, int32_t index, int32_t out[8]);
 

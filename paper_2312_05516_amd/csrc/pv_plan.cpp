@@ -46,6 +46,7 @@ Tuning default_tuning()
     t.wide_min_rows = env_int("PV_WIDE_MIN_ROWS", 33);
     t.xcds = env_int("PV_XCDS", 8);
     t.unify = env_int("PV_UNIFY", 1) == 1 ? 1 : 0;  // any other positive value switches it off
+    t.unify_max_steps = env_int("PV_UNIFY_MAX_STEPS", 90000);
     return t;
 }
 
@@ -263,11 +264,14 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
         }
     }
 
-    // One attention launch instead of two for a mixed batch.  An item of the matrix-core kernel
-    // holds a workgroup slot for one step per 32 keys whatever its row count, so a small unit
-    // (generation step) is cheaper in the bandwidth-oriented kernel; but a second launch has a
-    // fixed cost and the two kernels cannot share a CU.  When the matrix-core items are at least a
-    // fifth of all 32-key steps of the batch, everything goes to that kernel.
+    // One attention launch instead of two for a mixed batch.  Every launch has a fixed cost, the
+    // two kernels cannot share a CU, and a short bandwidth-oriented launch never gets the GPU up to
+    // speed, while its units fit well into the slots the long matrix-core items leave.  But an item
+    // of the matrix-core kernel holds a workgroup slot for one step per 32 keys whatever its row
+    // count, so when the small units (generation steps) are a large amount of work, the
+    // bandwidth-oriented kernel is the better place for them.  Measured crossover on mixes of
+    // 256-token prompts and generation steps over 2000-token contexts, MHA 40/40 and GQA 64/8 alike:
+    // 80-100 K steps of 32 keys summed over the small units and KV heads (~1.5 GB of K/V).
     bool all_wide = false;
     if (tune.unify) {
         int64_t wide_steps = 0, small_steps = 0;
@@ -284,7 +288,8 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
                 small_steps += (c + n + kKvBlock - 1) / kKvBlock;
             }
         }
-        all_wide = wide_steps > 0 && 4 * wide_steps >= small_steps;
+        all_wide = wide_steps > 0 &&
+                   small_steps * (int64_t)pool->num_kv_heads <= (int64_t)tune.unify_max_steps;
     }
     {
         // capacity for the item lists, so that filling them does not reallocate

@@ -67,8 +67,10 @@ struct Tuning {
     int32_t wide_min_rows;   // (request, KV head) units with n*G >= this use the matrix-core
                              // kernel; smaller ones are cut into 16-row items of the narrow kernel
     int32_t xcds;            // L2 domains the work list is interleaved over
-    int32_t unify;           // 1: a batch whose matrix-core work is a sizeable share sends its
-                             // small units to that kernel too (one attention launch, not two)
+    int32_t unify;           // 1: a batch with matrix-core work sends its small units to that
+                             // kernel too (one attention launch, not two) unless they are many
+    int32_t unify_max_steps; // "many": more than this many 32-key steps over all small units and
+                             // KV heads (then the bandwidth-oriented kernel is worth its launch)
 };
 
 }  // namespace pv

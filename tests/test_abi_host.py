@@ -126,20 +126,28 @@ def test_plan_splits_long_single_request(pv):
     plan.destroy()
 
 
-def test_plan_sends_small_units_to_the_matrix_core_kernel_when_prompts_dominate(pv):
-    """A mixed batch is one attention launch when the prompt work is at least a fifth of all 32-key
-    steps, two launches (generation steps in the bandwidth-oriented kernel) otherwise."""
-    desc = pv.pool_desc(4096, 4, 128, "f16")
-    # prompt of 200 tokens over 1000 cached: 2 tiles x 38 steps; generation steps: 2 x 32 steps
+def test_plan_sends_small_units_to_the_matrix_core_kernel_unless_they_are_many(pv):
+    """A mixed batch is one attention launch as long as its small units (generation steps) sum to at
+    most 90 K steps of 32 keys over all KV heads; beyond that they keep the bandwidth-oriented
+    kernel.  A batch without prompt work never uses the matrix-core kernel."""
+    desc = pv.pool_desc(1 << 17, 4, 128, "f16")
+    # a 200-token prompt next to two generation steps: 2 x 32 steps x 4 heads
     plan = pv.plan_create(desc, 4, [1000, 1000, 1000], [200, 1, 1], 128)
     assert pv.plan_num_work_items(plan, 0) == 0
     rows = sorted(int(it[3]) for it in _items(pv, plan, 1))
     assert rows[0] == 1 and rows[-1] == 128
     plan.destroy()
-    # the same prompt next to 40 generation steps over 4000 cached tokens each: 76 vs 5000 steps
-    plan = pv.plan_create(desc, 4, [1000] + [4000] * 40, [200] + [1] * 40, 256)
+    # the same prompt next to 100 generation steps over 8000 cached tokens: 100 K steps
+    plan = pv.plan_create(desc, 4, [1000] + [8000] * 100, [200] + [1] * 100, 512)
     assert pv.plan_num_work_items(plan, 0) > 0 and pv.plan_num_work_items(plan, 1) > 0
     assert all(int(it[3]) > 32 for it in _items(pv, plan, 1))
+    plan.destroy()
+    # 80 of them: 80 K steps, still one launch
+    plan = pv.plan_create(desc, 4, [1000] + [8000] * 80, [200] + [1] * 80, 512)
+    assert pv.plan_num_work_items(plan, 0) == 0
+    plan.destroy()
+    plan = pv.plan_create(desc, 4, [8000] * 3, [1] * 3, 512)
+    assert pv.plan_num_work_items(plan, 1) == 0
     plan.destroy()
 
 

@@ -296,20 +296,18 @@ def test_full_size_long_history(oracle):
 
 
 @pytest.mark.parametrize("kernels", ["one_attention_kernel", "two_attention_kernels"])
-def test_graph_replay_matches_eager(oracle, kernels):
+def test_graph_replay_matches_eager(oracle, kernels, monkeypatch):
     """The planned calls of a mixed batch (append, attention, the merge) captured into one HIP
     graph: every replay must reproduce the eager result bit for bit, with eager work and
-    synchronisations between the replays.  Two batches: one whose prompt work is large enough that
-    the plan sends the generation steps to the matrix-core kernel too, and one where the generation
-    steps dominate and keep their own kernel."""
+    synchronisations between the replays.  Once as the plan routes it (generation steps go to the
+    matrix-core kernel too) and once with the limit for that lowered so that they keep their own
+    kernel (the limit is read when the plan is created)."""
     import torch
     from paper_2312_05516_amd import binding as pv
-    if kernels == "one_attention_kernel":
-        b = wl.custom([700, 40, 2200, 5], [1, 70, 3, 150], num_q_heads=8, num_kv_heads=2,
-                      head_dim=128, dtype="bf16", seed=61)
-    else:
-        b = wl.custom([3000, 40, 4000, 5], [1, 40, 3, 1], num_q_heads=8, num_kv_heads=2,
-                      head_dim=128, dtype="bf16", seed=62)
+    b = wl.custom([700, 40, 2200, 5], [1, 70, 3, 150], num_q_heads=8, num_kv_heads=2,
+                  head_dim=128, dtype="bf16", seed=61)
+    if kernels == "two_attention_kernels":
+        monkeypatch.setenv("PV_UNIFY_MAX_STEPS", "10")
     case = H.make_case(b, fill="nan")
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
