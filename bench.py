@@ -27,21 +27,28 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 MFMA_PEAK_TFLOPS = 2500.0  # dense fp16 / bf16
 KERNEL_NAMES = {0: "attn_narrow_kernel", 1: "attn_wide_kernel", 2: "attn_combine_kernel",
-                3: "kv_append_kernel"}
+                3: "kv_append_kernel", 4: "attn_tile256_kernel"}
+# timing kind of an attention kernel -> kind of its work items in the plan
+ITEM_KIND = {0: 0, 1: 1, 4: 3}
+OTHER_WORKLOADS = "decode_heavy,gqa70b,mha13b"
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="mha13b",
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="long_history",
                     help="tiny | mha13b | gqa70b | long_history | decode_heavy | micro_c<ctx>")
     ap.add_argument("--layers", type=int, default=0, help="independent KV pools cycled through "
                     "(0 = pick so that the pools exceed 1 GiB of KV, at most 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0,
-                    help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="target CPU time of the oracle sample of the headline workload (the other "
+                    "workloads get a third of it each)")
+    ap.add_argument("--sustained-seconds", type=float, default=0.5,
+                    help="minimum timed wall time of the second, per-step-timed loop whose median "
+                    "and minimum are reported under 'sustained' (at least 50 steps)")
     ap.add_argument("--microbench", action="store_true",
                     help="instead of the step benchmark, time the attention call on the shape of the "
                     "paper's kernel figure (32 requests x 8 query tokens, context sweep) against our "
@@ -66,7 +73,7 @@ def parse_args():
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run plain device-to-device copies of this many GiB (untimed): the "
                     "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
-    ap.add_argument("--extra", default="gqa70b,long_history,decode_heavy",
+    ap.add_argument("--extra", default=OTHER_WORKLOADS,
                     help="comma list of further workloads to time briefly and report under "
                     "'other_workloads' ('none' for none)")
     return ap.parse_args()
@@ -115,7 +122,7 @@ class DeviceBatch:
             pv.plan_enable_timing(self.plan, True)
         self.ws = torch.empty(max(pv.plan_workspace_bytes(self.plan), 256), dtype=torch.uint8,
                               device=dev)
-        self.items = {k: pv.plan_num_work_items(self.plan, k) for k in (0, 1, 2)}
+        self.items = {k: pv.plan_num_work_items(self.plan, k) for k in (0, 1, 2, 3)}
         torch.cuda.synchronize()
         self.graphs = None
         if use_graph and not serial:
@@ -156,15 +163,43 @@ class DeviceBatch:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def sustained(self, min_seconds: float, min_steps: int = 50) -> dict:
+        """A second loop, long enough for the chip to settle at its power limit: at least
+        `min_steps` steps and `min_seconds` of timed wall time, every step bracketed by its own
+        pair of events on the launch stream; median, minimum and mean per step."""
+        torch = self.torch
+        for i in range(10):
+            self.run_step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(5):
+            self.run_step(i)
+        torch.cuda.synchronize()
+        est = max((time.perf_counter() - t0) / 5, 1e-6)
+        n = int(max(min_steps, min(20000, np.ceil(min_seconds / est))))
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        t0 = time.perf_counter()
+        ev[0].record()
+        for i in range(n):
+            self.run_step(i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(n)])
+        return {"steps": n, "wall_seconds": round(wall, 3), "median_ms": round(float(np.median(ms)), 5),
+                "min_ms": round(float(ms.min()), 5), "mean_ms": round(float(ms.mean()), 5),
+                "tflops_at_median": round(self.b.flops() / float(np.median(ms)) / 1e9, 2),
+                "kv_gbps_at_median": round(self.b.kv_bytes() / float(np.median(ms)) / 1e6, 1)}
+
     def kernel_times(self, steps: int) -> dict:
         """Average duration of each kernel over `steps` instrumented steps (HIP events recorded by
         the library on the launch stream around every kernel)."""
         pv = self.pv
         pv.plan_enable_timing(self.plan, True)
-        acc = {k: [] for k in range(4)}
+        acc = {k: [] for k in KERNEL_NAMES}
         for i in range(steps):
             self.step(i)
-            for k in range(4):
+            for k in KERNEL_NAMES:
                 ms = pv.plan_kernel_ms(self.plan, k)
                 if ms >= 0:
                     acc[k].append(ms)
@@ -172,19 +207,34 @@ class DeviceBatch:
         return {k: float(np.mean(v)) for k, v in acc.items() if v}
 
     def kernel_share(self, kind: int):
-        """Algorithmic flops and bytes of the requests whose rows run in attention kernel `kind`."""
+        """Algorithmic flops and bytes of the work items of attention kernel `kind`: causal
+        (row, key) pairs inside the items' KV ranges counted exactly; every (request, KV head)
+        K/V range the kernel streams counted once, plus its rows of q and out and the page ids."""
         pv, b = self.pv, self.b
-        reqs = set()
-        for i in range(self.items[kind]):
-            reqs.add(int(pv.plan_work_item(self.plan, kind, i)[0]))
-        idx = np.array(sorted(reqs), dtype=np.int64)
-        c = b.ctx_lens[idx].astype(np.int64)
-        n = b.q_lens[idx].astype(np.int64)
-        pairs = int((n * c + n * (n + 1) // 2).sum())
-        flops = 4 * b.head_dim * b.num_q_heads * pairs
-        kv = int(2 * (c + n).sum() * b.num_kv_heads * b.head_dim * 2)
-        qo = int(2 * n.sum() * b.num_q_heads * b.head_dim * 2)
-        pt = int(4 * np.ceil((c + n) / b.page_size).sum())
+        n = self.items[ITEM_KIND[kind]]
+        if n == 0:
+            return 0, 0
+        it = np.stack([pv.plan_work_item(self.plan, ITEM_KIND[kind], i) for i in range(n)]).astype(np.int64)
+        req, hk, rb, rc, k0, k1 = (it[:, j] for j in range(6))
+        G = b.num_q_heads // b.num_kv_heads
+        ctx = b.ctx_lens[req].astype(np.int64)
+        pairs = 0
+        for j in range(int(rc.max())):  # j-th row of every item that has one
+            m = rc > j
+            lim = np.minimum(k1[m], ctx[m] + (rb[m] + j) // G + 1)
+            pairs += int(np.maximum(lim - k0[m], 0).sum())
+        flops = 4 * b.head_dim * pairs
+        # K/V streamed: per (request, KV head) the union of the items' ranges = [min k0, max k1)
+        unit = req * b.num_kv_heads + hk
+        lo = np.full(b.num_reqs * b.num_kv_heads, np.iinfo(np.int64).max)
+        hi = np.zeros(b.num_reqs * b.num_kv_heads, dtype=np.int64)
+        np.minimum.at(lo, unit, k0)
+        np.maximum.at(hi, unit, k1)
+        span = np.maximum(hi - np.minimum(lo, hi), 0)
+        kv = int(2 * span.sum() * b.head_dim * 2)
+        first = it[:, 6] == 0  # rows are counted once per item set, not once per KV part
+        qo = int(2 * rc[first].sum() * b.head_dim * 2)
+        pt = int(4 * np.ceil(span / b.page_size).sum())
         return flops, kv + qo + pt
 
     def close(self):
@@ -193,7 +243,8 @@ class DeviceBatch:
 
 
 def recorded_traffic(workload: str, kernel: str):
-    """HBM bytes per launch measured earlier with rocprofv3 --pmc (profiles/traffic.txt), or None."""
+    """HBM bytes per launch measured earlier with rocprofv3 --pmc (profiles/traffic.txt), or None.
+    Not measured in this run: the line says so in `traffic_source`."""
     path = os.path.join(ROOT, "profiles", "traffic.txt")
     try:
         for line in open(path):
@@ -206,7 +257,7 @@ def recorded_traffic(workload: str, kernel: str):
 
 
 def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
-    attn = {k: v for k, v in ktimes.items() if k in (0, 1)}
+    attn = {k: v for k, v in ktimes.items() if k in ITEM_KIND}
     if not attn:
         return None
     kind = max(attn, key=attn.get)
@@ -215,17 +266,19 @@ def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
     t_hbm = nbytes / (HBM_PEAK_GBPS * 1e9)
     t_mfma = flops / (MFMA_PEAK_TFLOPS * 1e12)
     traffic = recorded_traffic(db.b.name, KERNEL_NAMES[kind])
+    common = {"traffic": traffic,
+              "traffic_source": None if traffic is None else
+              "recorded earlier with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/traffic.txt), "
+              "not measured in this run",
+              "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
+              "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
     if t_hbm >= t_mfma:
         ach = nbytes / t / 1e9
         return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
-                "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
+                "frac": round(ach / HBM_PEAK_GBPS, 4), **common}
     ach = flops / t / 1e12
     return {"bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": round(ach / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
-            "kernel": KERNEL_NAMES[kind], "kernel_ms": round(attn[kind], 5),
-            "algorithmic_bytes": nbytes, "algorithmic_flops": flops}
+            "frac": round(ach / MFMA_PEAK_TFLOPS, 4), **common}
 
 
 def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
@@ -244,20 +297,27 @@ def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
     c = b.ctx_lens.astype(np.int64)
     n = b.q_lens.astype(np.int64)
     unit_flops = 4 * D * G * (n * c + n * (n + 1) // 2)  # per (request, KV head)
+    # stratified sample: the (request, KV head) units sorted by cost, every k-th of them (KV head
+    # chosen by a seeded draw), k such that the sample fits the budget; at least one unit
     rng = np.random.default_rng(b.seed + 99)
-    order = rng.permutation(b.num_reqs * Hkv)
+    live = [r for r in np.argsort(unit_flops, kind="stable") if n[r] > 0]
+    all_units = [(int(r), int(h)) for r in live for h in rng.permutation(Hkv)]
+    all_units.sort(key=lambda rh: (int(unit_flops[rh[0]]), rh[0]))
+    total_all = sum(int(unit_flops[r]) for r, _ in all_units)
+    stride = max(1, int(np.ceil(total_all / max(budget_flops, 1.0))))
+    page_bytes = 2 * Hkv * b.page_size * D * 2  # K and V image of one page, all KV heads
+    while True:  # the sampled requests' pages are copied to the host: keep that under 4 GB
+        picked = all_units[stride // 2::stride] or all_units[:1]
+        host_bytes = sum(int(np.ceil(b.kv_lens[r] / b.page_size)) * page_bytes
+                         for r in {r for r, _ in picked})
+        if host_bytes <= 4e9 or len(picked) == 1:
+            break
+        stride *= 2
     mask = np.zeros((b.num_reqs, Hkv), dtype=np.uint8)
     total = 0
-    for u in order:
-        r, h = divmod(int(u), Hkv)
-        if n[r] == 0:
-            continue
-        if total > 0 and total + unit_flops[r] > budget_flops:
-            continue
+    for r, h in picked:
         mask[r, h] = 1
         total += int(unit_flops[r])
-        if total >= 0.9 * budget_flops:
-            break
     reqs = [r for r in range(b.num_reqs) if mask[r].any()]
     # compact host copy of the sampled requests' pages (layer 0 pools, after the append)
     pages, remap = [], {}
@@ -288,29 +348,37 @@ def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
     units = int(mask.sum())
     return {"value": round(total / dt / 1e12, 6), "unit": "TFLOP/s", "cores": info["threads"],
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"{units} of {b.num_reqs * Hkv} (request, KV head) units of {b.name}, "
-                      f"{total / 1e9:.2f} GFLOP, fp64 C oracle with OpenMP, attention only"}
+            "sample": f"{units} of {b.num_reqs * Hkv} (request, KV head) units of {b.name} "
+                      f"(every {stride}-th unit in order of cost), {total / 1e9:.2f} GFLOP, "
+                      f"fp64 C oracle with OpenMP, attention only"}
 
 
 def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool,
-                 cpu_seconds: float, serial: bool = False, use_graph: bool = True) -> dict:
+                 cpu_seconds: float, serial: bool = False, use_graph: bool = True,
+                 sustained_seconds: float = 0.5) -> dict:
     b = make_batch(name)
     db = DeviceBatch(b, layers, serial, use_graph)
     ms = db.time_steps(steps, warmup)
-    ktimes = db.kernel_times(min(steps, 50))
+    sustained = db.sustained(sustained_seconds) if sustained_seconds > 0 else None
+    ktimes = db.kernel_times(50)
     roof = roofline_for(db, ktimes)
     res = {
         "workload": name,
+        "dtype": b.dtype,
         "ms_per_step": round(ms, 5),
         "tflops": round(b.flops() / (ms * 1e-3) / 1e12, 3),
         "kv_gbps": round(b.kv_bytes() / (ms * 1e-3) / 1e9, 1),
         "algorithmic_gbps": round(b.algorithmic_bytes() / (ms * 1e-3) / 1e9, 1),
+        "steps": steps,
+        "warmup": warmup,
+        "sustained": sustained,
         "kernel_ms": {KERNEL_NAMES[k]: round(v, 5) for k, v in ktimes.items()},
         "roofline": roof,
         "plan_ms": round(db.plan_ms, 3),
         "layers": db.layers,
         "launch": "hipgraph" if db.graphs is not None else "eager",
-        "items": {"narrow": db.items[0], "wide": db.items[1], "combine": db.items[2]},
+        "items": {"narrow": db.items[0], "wide": db.items[1], "tile256": db.items[3],
+                  "combine": db.items[2]},
         "batch": {"requests": b.num_reqs, "new_tokens": b.total_q,
                   "kv_tokens": int(b.kv_lens.sum()), "flops": b.flops(), "kv_bytes": b.kv_bytes()},
     }
@@ -576,16 +644,20 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    main_res = run_workload(args.workload, args.steps, args.warmup, args.layers,
-                            not args.no_cpu_baseline, args.cpu_seconds, args.serial_kernels,
-                            not args.no_graph)
+    with_cpu = not args.no_cpu_baseline
+    main_res = run_workload(args.workload, args.steps, args.warmup, args.layers, with_cpu,
+                            args.cpu_seconds, args.serial_kernels, not args.no_graph,
+                            args.sustained_seconds)
     b = make_batch(args.workload)
     others = []
-    for name in [x for x in args.extra.split(",") if x and x != "none"]:
-        r = run_workload(name, max(10, args.steps // 4), max(3, args.warmup // 4), 0, False, 0,
-                         False, not args.no_graph)
-        others.append({k: r[k] for k in ("workload", "ms_per_step", "tflops", "kv_gbps",
-                                         "kernel_ms", "roofline", "items")})
+    for name in [x for x in args.extra.split(",") if x and x != "none" and x != args.workload]:
+        # the same number of steps and warm-up steps as the headline, bounded to ~0.5 s per loop
+        r = run_workload(name, args.steps, args.warmup, 0, with_cpu, args.cpu_seconds / 3, False,
+                         not args.no_graph, args.sustained_seconds)
+        others.append({k: r[k] for k in ("workload", "dtype", "ms_per_step", "tflops", "kv_gbps",
+                                         "steps", "warmup", "sustained", "kernel_ms", "roofline",
+                                         "items", "plan_ms") if k in r}
+                      | ({"cpu_baseline": r["cpu_baseline"]} if "cpu_baseline" in r else {}))
     line = {
         "metric": "multi-token paged attn TFLOP/s + effective KV GB/s (1 MI355X, % roofline)",
         "value": main_res["tflops"],
@@ -608,6 +680,7 @@ def main():
                    "launch": main_res["launch"]},
         "roofline": main_res["roofline"],
         "cpu_baseline": main_res.get("cpu_baseline"),
+        "sustained": main_res["sustained"],
         "kernel_ms": main_res["kernel_ms"],
         "plan_ms": main_res["plan_ms"],
         "items": main_res["items"],

@@ -24,6 +24,9 @@
  *     host copy.
  *   - A plan may be shared by the launches of many layers, but by one host thread at a time (a
  *     launch updates the plan's timing state and, the first time, uploads it).
+ *   - Alignment: q, out, k_new, v_new, the pools and the rotary table are read and written with
+ *     16-byte vector accesses: every such pointer must be 16-byte aligned (the launching calls
+ *     return PV_ERR_INVALID_ARG otherwise); a workspace must be 256-byte aligned.
  *   - Supported: page_size 16; head_dim 64 or 128; dtype f16 or bf16;
  *     num_q_heads a multiple of num_kv_heads (consecutive query heads
  *     hq = hk*G .. hk*G+G-1 share KV head hk, G = num_q_heads/num_kv_heads).
@@ -91,8 +94,8 @@ int64_t pv_pool_v_offset(const pv_pool_desc *pool, int32_t page, int32_t head, i
 
 /*
  * Auxiliary arrays of a batch (paper Section 6.4: cumulative sequence lengths and the like are
- * computed once on the CPU and shared by all layers; Section 4.4.1: "some auxiliary data
- * structure ... keeps track of each request's region").
+ * computed once on the CPU and shared by all layers; Section 4.4.1: the batch carries a record of
+ * which rows of the concatenated tokens belong to which request).
  *
  * pv_plan_create is pure host code: it validates the lengths, computes
  * q_start = exclusive prefix sum of q_lens, and splits the work of the batch into the work

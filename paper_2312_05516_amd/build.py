@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpv.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["pv_plan.cpp", "pv_lib.hip", "pv_append.hip", "pv_attn_narrow.hip", "pv_attn_wide.hip",
+SOURCES = ["pv_plan.cpp", "pv_lib.hip", "pv_append.hip", "pv_attn_narrow.hip", "pv_attn_wide.hip", "pv_attn_tile256.hip",
            "pv_swap.hip", "pv_rope.hip"]
 # packed fp32 VALU forms are switched off for every device compile
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

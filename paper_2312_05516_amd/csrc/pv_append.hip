@@ -40,24 +40,7 @@ __global__ __launch_bounds__(D) void kv_append_kernel(
         }
     }
     // V: thread -> head dimension d = t
-    {
-        uint16_t vals[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vals[j] = j < g.count ? vsrc[j * row_stride + t] : (uint16_t)0;
-        uint16_t *vdst = v_pages + tile + ((int64_t)((slot0 >> 3) * D + t) * 8);
-        if (g.count == 8) {
-            u32x4 packed;
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                packed[jj] = (uint32_t)vals[2 * jj] | ((uint32_t)vals[2 * jj + 1] << 16);
-            *reinterpret_cast<u32x4 *>(vdst) = packed;
-        } else {
-            const int s0 = slot0 & 7;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (j < g.count) vdst[s0 + j] = vals[j];
-        }
-    }
+    scatter_v_group<D>(vsrc, row_stride, g.count, slot0, t, v_pages + tile);
 }
 
 hipError_t launch_kv_append(const pv_plan *plan, const void *k_new, const void *v_new,

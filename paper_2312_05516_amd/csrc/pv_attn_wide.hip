@@ -2,8 +2,8 @@
 // query heads of a GQA group) that share one KV head's K/V stream.
 //
 // Computes paper Eq. 2-3 with the causal rule of Section 4.4 for the rows of one item over the
-// item's KV range, reading K and V through the page table: the "two matrix-matrix
-// multiplications" with fused mask of Section 4.4, fused flash-style so that the score matrix is
+// item's KV range, reading K and V through the page table: the pair of matrix products with the
+// fused causal mask that Section 4.4 describes, fused flash-style so that the score matrix is
 // never materialised.
 //
 // Mapping to gfx950.  One workgroup = 4 wavefronts = one item; wavefront w owns rows 32w..32w+31.

@@ -101,8 +101,9 @@ typedef __attribute__((address_space(3))) void *lds_void_ptr;
 // lds_base + 16*l.  Issued as raw instructions so that the compiler's wait-count insertion does
 // not serialise it against unrelated LDS reads; completion is awaited explicitly (vmcnt) before the
 // barrier that publishes the stage.  lds_base must be wavefront-uniform.  The statement rewrites
-// M0, which the compiler never keeps live across statements in these kernels (it reloads M0 next
-// to every instruction that needs it).
+// M0.  M0 is a reserved register for this compiler: it never carries a value from one instruction
+// to a later one (every instruction that needs M0 gets its own s_mov in front), and it rejects M0
+// in a clobber list for that reason, so none is given.
 __device__ __forceinline__ void lds_dma16(const void *uniform_base, uint32_t lane_offset,
                                           void *lds_base)
 {
@@ -112,6 +113,34 @@ __device__ __forceinline__ void lds_dma16(const void *uniform_base, uint32_t lan
                  :
                  : "s"(lds_addr), "v"(lane_offset), "s"(uniform_base)
                  : "memory");
+}
+
+// V part of the KV append, shared by the plain and the rotary-fused append kernels so that the
+// bit-exact path exists once.  Thread d (of D) owns head dimension d of one (page, head) tile:
+// it gathers that dimension from the `count` (1..8) consecutive new tokens of an append group
+// (rows of `vsrc`, `row_stride` elements apart) and stores them at slots slot0 .. slot0+count-1,
+// which lie inside one 8-slot run of the V tile.  A full run is one 16-byte store; a partial one
+// is written element by element so that the other slots keep their contents.
+template <int D>
+__device__ __forceinline__ void scatter_v_group(const uint16_t *vsrc, int64_t row_stride,
+                                                int count, int slot0, int d, uint16_t *v_tile)
+{
+    uint16_t vals[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vals[j] = j < count ? vsrc[j * row_stride + d] : (uint16_t)0;
+    uint16_t *vdst = v_tile + ((int64_t)((slot0 >> 3) * D + d) * 8);
+    if (count == 8) {
+        u32x4 packed;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+            packed[jj] = (uint32_t)vals[2 * jj] | ((uint32_t)vals[2 * jj + 1] << 16);
+        *reinterpret_cast<u32x4 *>(vdst) = packed;
+    } else {
+        const int s0 = slot0 & 7;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (j < count) vdst[s0 + j] = vals[j];
+    }
 }
 
 // s_waitcnt immediate (gfx9 encoding): wait until at most `vm` vector-memory operations and at most

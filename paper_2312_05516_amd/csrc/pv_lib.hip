@@ -18,6 +18,9 @@ hipError_t launch_attn_narrow(const pv_plan *plan, const void *q, const void *k_
 hipError_t launch_attn_wide(const pv_plan *plan, const void *q, const void *k_pages,
                             const void *v_pages, const int32_t *page_table, float scale, void *out,
                             float *ws_o, float *ws_ml, hipStream_t stream);
+hipError_t launch_attn_tile256(const pv_plan *plan, const void *q, const void *k_pages,
+                               const void *v_pages, const int32_t *page_table, float scale,
+                               void *out, float *ws_o, float *ws_ml, hipStream_t stream);
 hipError_t launch_attn_combine(const pv_plan *plan, const float *ws_o, const float *ws_ml,
                                void *out, hipStream_t stream);
 
@@ -40,7 +43,7 @@ static pv_status upload(pv_plan *plan)
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
     struct Part { const void *src; size_t bytes; size_t off; };
-    Part parts[8] = {
+    Part parts[9] = {
         {plan->ctx_lens.data(), plan->ctx_lens.size() * sizeof(int32_t), 0},
         {plan->q_lens.data(), plan->q_lens.size() * sizeof(int32_t), 0},
         {plan->q_start.data(), plan->q_start.size() * sizeof(int32_t), 0},
@@ -49,6 +52,7 @@ static pv_status upload(pv_plan *plan)
         {plan->wide.data(), plan->wide.size() * sizeof(WorkItem), 0},
         {plan->combine.data(), plan->combine.size() * sizeof(CombineItem), 0},
         {plan->append_groups.data(), plan->append_groups.size() * sizeof(AppendGroup), 0},
+        {plan->tile256.data(), plan->tile256.size() * sizeof(WorkItem), 0},
     };
     size_t total = 0;
     for (Part &p : parts) {
@@ -75,6 +79,7 @@ static pv_status upload(pv_plan *plan)
     plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
     plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
     plan->d_append_groups = reinterpret_cast<AppendGroup *>(b + parts[7].off);
+    plan->d_tile256 = reinterpret_cast<WorkItem *>(b + parts[8].off);
     plan->device = dev;
     plan->uploaded = true;
     return PV_OK;
@@ -132,7 +137,7 @@ pv_status pv_plan_enable_timing(pv_plan *plan, int32_t enable)
 
 pv_status pv_plan_kernel_ms(pv_plan *plan, int32_t kind, float *ms)
 {
-    if (!plan || !ms || kind < 0 || kind > 3) return PV_ERR_INVALID_ARG;
+    if (!plan || !ms || kind < 0 || kind > 4) return PV_ERR_INVALID_ARG;
     *ms = -1.f;
     if (!plan->events[0] || !plan->event_used[kind]) return PV_OK;
     hipEvent_t a = static_cast<hipEvent_t>(plan->events[2 * kind]);
@@ -221,7 +226,13 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
     pv_status s = pv::ensure_ready(plan);
     if (s != PV_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // the kernels touch disjoint rows of `out`; both run on the caller's stream
+    // the kernels touch disjoint rows of `out`; all run on the caller's stream
+    {
+        pv::KernelTimer t(plan, 4, st, !plan->tile256.empty());
+        if (pv::launch_attn_tile256(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+                                    ws_ml, st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
     {
         pv::KernelTimer t(plan, 1, st, !plan->wide.empty());
         if (pv::launch_attn_wide(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
@@ -334,14 +345,15 @@ size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, in
         return 0;
     // Splitting only happens while a kernel has fewer items than the target and never makes a
     // part shorter than half the target share, so each kernel ends with fewer than
-    // items + split_target parts of at most 16 resp. kWideRows rows.  Independently, a row can be
+    // items + split_target parts of at most 16, kWideRows resp. kTileRows rows.  Independently, a row can be
     // in at most max_kv_len / min_split_keys + 1 parts.
     const pv::Tuning t = pv::default_tuning();
     const int64_t rows = (int64_t)total_q * num_q_heads +
                          (int64_t)num_reqs * pool->num_kv_heads * pv::kNarrowRows;
     const int64_t max_parts = (int64_t)max_kv_len / t.min_split_keys + 1;
     const int64_t by_rows = rows * max_parts;
-    const int64_t by_items = 2 * (int64_t)t.split_target * (pv::kNarrowRows + pv::kWideRows);
+    const int64_t by_items =
+        2 * (int64_t)t.split_target * (pv::kNarrowRows + pv::kWideRows + pv::kTileRows);
     const int64_t slots = by_rows < by_items ? by_rows : by_items;
     return (size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float);
 }

@@ -47,7 +47,20 @@ Tuning default_tuning()
     t.xcds = env_int("PV_XCDS", 8);
     t.unify = env_int("PV_UNIFY", 1) == 1 ? 1 : 0;  // any other positive value switches it off
     t.unify_max_steps = env_int("PV_UNIFY_MAX_STEPS", 90000);
+    {
+        const char *v = std::getenv("PV_TILE_MIN_KEYS");
+        t.tile_min_keys = (v && *v == '0' && !v[1]) ? 0 : env_int("PV_TILE_MIN_KEYS", 0);
+    }
     return t;
+}
+
+// Whether the full 256-row tiles of a (request, KV head) unit go to the 256-row kernel: that
+// kernel exists for head size 128 and pays off when an item streams many 32-key blocks.
+static bool use_tile256(const pv_pool_desc *pool, const Tuning &tune, int64_t rows_total,
+                        int64_t kv_len)
+{
+    return tune.tile_min_keys > 0 && pool->head_dim == 128 && rows_total >= kTileRows &&
+           kv_len >= tune.tile_min_keys;
 }
 
 static int64_t item_cost(const WorkItem &w, int rows_per_step)
@@ -322,7 +335,17 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
             w.ctx = c;
             const bool use_wide = rows_total >= tune.wide_min_rows || all_wide;
             const int32_t tile = use_wide ? kWideRows : kNarrowRows;
-            for (int32_t rb = 0; rb < rows_total; rb += tile) {
+            // long units: their full 256-row tiles go to the 256-row kernel, the rest as usual
+            int32_t rb = 0;
+            if (use_tile256(pool, tune, rows_total, (int64_t)c + n)) {
+                for (; rb + kTileRows <= rows_total; rb += kTileRows) {
+                    w.row_begin = rb;
+                    w.row_count = kTileRows;
+                    w.kv_end = c + (rb + kTileRows - 1) / G + 1;
+                    plan->tile256.push_back(w);
+                }
+            }
+            for (; rb < rows_total; rb += tile) {
                 w.row_begin = rb;
                 w.row_count = std::min(tile, rows_total - rb);
                 const int32_t last_token = (rb + w.row_count - 1) / G;
@@ -334,12 +357,14 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     int64_t slots = 0;
     split_items(plan->narrow, plan->combine, slots, tune);
     split_items(plan->wide, plan->combine, slots, tune);
+    split_items(plan->tile256, plan->combine, slots, tune);
     if (slots > INT32_MAX / 2) {
         delete plan;
         return PV_ERR_OUT_OF_RANGE;
     }
     order_items(plan->narrow, kNarrowRows, tune.xcds);
     order_items(plan->wide, env_int("PV_WIDE_COST_ROWS", kWideRows), tune.xcds);
+    order_items(plan->tile256, kTileRows, tune.xcds);
     plan->partial_slots = slots;
     for (size_t i = 0; i < plan->combine.size(); ++i)
         for (int32_t r0 = 0; r0 < plan->combine[i].row_count; r0 += 8)
@@ -424,6 +449,7 @@ int32_t pv_plan_num_work_items(const pv_plan *plan, int32_t kind)
     case 0: return (int32_t)plan->narrow.size();
     case 1: return (int32_t)plan->wide.size();
     case 2: return (int32_t)plan->combine.size();
+    case 3: return (int32_t)plan->tile256.size();
     }
     return -1;
 }
@@ -431,8 +457,9 @@ int32_t pv_plan_num_work_items(const pv_plan *plan, int32_t kind)
 pv_status pv_plan_work_item(const pv_plan *plan, int32_t kind, int32_t index, int32_t out[8])
 {
     if (!plan || !out || index < 0) return PV_ERR_INVALID_ARG;
-    if (kind == 0 || kind == 1) {
-        const std::vector<pv::WorkItem> &v = kind == 0 ? plan->narrow : plan->wide;
+    if (kind == 0 || kind == 1 || kind == 3) {
+        const std::vector<pv::WorkItem> &v =
+            kind == 0 ? plan->narrow : kind == 1 ? plan->wide : plan->tile256;
         if ((size_t)index >= v.size()) return PV_ERR_INVALID_ARG;
         const pv::WorkItem &w = v[index];
         const int32_t f[8] = {w.req, w.kv_head, w.row_begin, w.row_count,

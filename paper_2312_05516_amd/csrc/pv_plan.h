@@ -59,6 +59,7 @@ static_assert(sizeof(AppendGroup) == 16, "AppendGroup is read by the kernel as 4
 
 constexpr int kNarrowRows = 16;  // rows per item of the bandwidth-oriented kernel
 constexpr int kWideRows = 128;   // rows per item of the matrix-core kernel (4 waves x 32 rows)
+constexpr int kTileRows = 256;   // rows per item of the 256-row matrix-core kernel (4 waves x 64)
 constexpr int kKvBlock = 32;     // keys per inner step (two pages)
 
 struct Tuning {
@@ -71,6 +72,9 @@ struct Tuning {
                              // kernel too (one attention launch, not two) unless they are many
     int32_t unify_max_steps; // "many": more than this many 32-key steps over all small units and
                              // KV heads (then the bandwidth-oriented kernel is worth its launch)
+    int32_t tile_min_keys;   // (request, KV head) units with at least 256 rows and at least this
+                             // many keys send their full 256-row tiles to the 256-row kernel
+                             // (0 switches that kernel off)
 };
 
 }  // namespace pv
@@ -83,7 +87,7 @@ struct pv_plan {
     int32_t max_pages_per_req;
     int32_t total_q;
     std::vector<int32_t> ctx_lens, q_lens, q_start;
-    std::vector<pv::WorkItem> narrow, wide;
+    std::vector<pv::WorkItem> narrow, wide, tile256;
     std::vector<pv::CombineItem> combine;
     std::vector<pv::AppendGroup> append_groups;
     std::vector<pv::CombineChunk> combine_chunks;
@@ -95,15 +99,15 @@ struct pv_plan {
     int device;
     void *d_blob;  // one allocation holding everything below
     int32_t *d_ctx_lens, *d_q_lens, *d_q_start;
-    pv::WorkItem *d_narrow, *d_wide;
+    pv::WorkItem *d_narrow, *d_wide, *d_tile256;
     pv::CombineItem *d_combine;
     pv::AppendGroup *d_append_groups;
     pv::CombineChunk *d_combine_chunks;
 
     // optional per-kernel timing: events[2*kind], events[2*kind+1] bracket kernel `kind`
     bool timing;
-    void *events[8];
-    bool event_used[4];
+    void *events[10];
+    bool event_used[5];
 };
 
 namespace pv {

@@ -34,8 +34,8 @@ __device__ __forceinline__ u32x4 pack8(const float (&x)[8])
 
 template <typename T, int D, int STYLE>
 __global__ __launch_bounds__(D) void rope_append_kernel(
-    const AppendGroup *__restrict__ groups, const uint16_t *__restrict__ q_in,
-    uint16_t *__restrict__ q_out, const uint16_t *__restrict__ k_new,
+    const AppendGroup *__restrict__ groups, const uint16_t *q_in,
+    uint16_t *q_out /* may be q_in */, const uint16_t *__restrict__ k_new,
     const uint16_t *__restrict__ v_new, const float *__restrict__ cos_sin,
     const int32_t *__restrict__ page_table, int32_t max_pages, int32_t num_q_heads,
     int32_t num_kv_heads, uint16_t *__restrict__ k_pages, uint16_t *__restrict__ v_pages)
@@ -106,24 +106,9 @@ __global__ __launch_bounds__(D) void rope_append_kernel(
     }
 
     if (!is_q) {
-        // V: thread -> head dimension d = t (same as kv_append_kernel)
+        // V: thread -> head dimension d = t, moved bit for bit
         const uint16_t *vsrc = v_new + (int64_t)g.q_row * row_stride + (int64_t)head * D;
-        uint16_t vals[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vals[j] = j < g.count ? vsrc[j * row_stride + t] : (uint16_t)0;
-        uint16_t *vdst = v_pages + tile + ((int64_t)((slot0 >> 3) * D + t) * 8);
-        if (g.count == 8) {
-            u32x4 packed;
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                packed[jj] = (uint32_t)vals[2 * jj] | ((uint32_t)vals[2 * jj + 1] << 16);
-            *reinterpret_cast<u32x4 *>(vdst) = packed;
-        } else {
-            const int s0 = slot0 & 7;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (j < g.count) vdst[s0 + j] = vals[j];
-        }
+        scatter_v_group<D>(vsrc, row_stride, g.count, slot0, t, v_pages + tile);
     }
 }
 

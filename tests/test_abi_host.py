@@ -53,8 +53,9 @@ def _items(pv, plan, kind):
     return [pv.plan_work_item(plan, kind, i) for i in range(pv.plan_num_work_items(plan, kind))]
 
 
-@pytest.mark.parametrize("name", ["tiny", "mha13b", "gqa70b", "decode_heavy"])
-def test_plan_covers_every_row_exactly_once(pv, name):
+@pytest.mark.parametrize("name", ["tiny", "mha13b", "gqa70b", "decode_heavy", "long_history"])
+def test_plan_covers_every_row_exactly_once(pv, name, monkeypatch):
+    monkeypatch.setenv("PV_TILE_MIN_KEYS", "2048")
     b = wl.CONFIGS[name]()
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
@@ -63,10 +64,13 @@ def test_plan_covers_every_row_exactly_once(pv, name):
     G = b.num_q_heads // b.num_kv_heads
     # for every (req, kv head, row): the KV parts that contain it must tile [0, causal limit)
     cover = {}
-    for kind in (0, 1):
+    for kind in (0, 1, 3):
         for it in _items(pv, plan, kind):
             req, hk, rb, rc, k0, k1, si, sc = (int(x) for x in it)
-            assert 0 < rc <= (16 if kind == 0 else 128)
+            assert 0 < rc <= {0: 16, 1: 128, 3: 256}[kind]
+            if kind == 3:  # the 256-row kernel only takes full tiles of long units, head size 128
+                assert rc == 256 and rb % 256 == 0 and b.head_dim == 128
+                assert b.ctx_lens[req] + b.q_lens[req] >= 2048
             assert k0 % 32 == 0 and k0 < k1
             last_tok = (rb + rc - 1) // G
             assert k1 <= b.ctx_lens[req] + last_tok + 1
@@ -92,7 +96,7 @@ def test_plan_covers_every_row_exactly_once(pv, name):
     plan.destroy()
 
 
-def test_plan_orders_items_longest_first_per_xcd(pv):
+def test_plan_orders_items_longest_first_per_xcd(pv, monkeypatch):
     """Workgroup i goes to XCD i % 8: every XCD sees its items longest first, and the tiles of one
     (request, KV head) sit on one XCD."""
     b = wl.decode_heavy()
@@ -105,10 +109,12 @@ def test_plan_orders_items_longest_first_per_xcd(pv):
         assert q == sorted(q, reverse=True)
     plan.destroy()
     b = wl.long_history()
+    monkeypatch.setenv("PV_TILE_MIN_KEYS", "2048")
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
-    items = _items(pv, plan, 1)
-    assert len(items) == 8 * 8 * 32
+    assert pv.plan_num_work_items(plan, 1) == 0
+    items = _items(pv, plan, 3)
+    assert len(items) == 8 * 8 * 16
     home = {}
     for i, it in enumerate(items):
         home.setdefault((int(it[0]), int(it[1])), set()).add(i % 8)
