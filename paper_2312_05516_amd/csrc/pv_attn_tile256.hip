@@ -13,24 +13,37 @@
 //    flop) and a K/V tile fetched from L2 serves 256 rows (half the L2 -> LDS traffic per flop of
 //    the 128-row kernel).  On this chip long matrix-core kernels run against the power limit, so
 //    data movement saved is clock frequency gained.
-//  * Software pipeline inside the wavefront: iteration b issues, in one basic block, the score
-//    product of block b+1 (16 matrix-core instructions), the exponentials of block b (vector ALU)
-//    and the value product of block b (16 more), so the matrix cores and the vector ALU of the SIMD
-//    overlap without relying on other wavefronts.  The rare running-maximum update (lazy, as in
-//    attn_wide_kernel) is a branch at the end of the iteration and works on block b+1's scores.
+//  * With one wavefront per SIMD nothing else hides a stall, and every instruction of any kind
+//    costs that wavefront four to five issue cycles (measured), of which about 27 are free next
+//    to a 32-cycle matrix-core instruction.  So the steady-state iteration is a hand-laid
+//    schedule of 32 slots, one matrix-core instruction each, software-pipelined: slot by slot it
+//    issues the score product of block b+1, the exponentials of block b and the value product of
+//    block b (see fast_step).  The instruction count per slot is what is tuned:
+//      - for the usual small scales the queries are pre-multiplied by scale*log2(e) once (rounded
+//        to the 16-bit type; see PRE below) and the score product starts from minus the row's
+//        reference maximum instead of zero, so a probability is one exp2 of a matrix-core result;
+//      - row sums use v_dot2 on the packed probabilities, but all sixteen at the end of the
+//        iteration: a dot instruction waits for the matrix pipe to drain, once per cluster;
+//      - addresses of the asynchronous copies are two scalar multiplies and four 64-bit adds.
 //  * K/V page tiles go HBM/L2 -> LDS directly (global_load_lds) into a ring of 8 stages, six blocks
 //    ahead; one s_barrier per block.  K operands of block b+2 are requested before the barrier at
 //    the end of iteration b, so they are in registers when iteration b+1 starts.
 //
 // Blocks that touch the causal boundary or the end of the sequence run in a second, masked loop
 // with the same barrier protocol, so the wavefronts of a workgroup stay in step.
+//
+// PRE (template flag, chosen per launch): the queries are multiplied by scale*log2(e) and rounded
+// back to 16 bits when they are loaded.  That rounding moves a score by at most 2^-9 (bf16) or
+// 2^-12 (fp16) of sum_d |q_d k_d| * scale*log2(e), the size of the rounding the probabilities get
+// anyway before the second product; the launch uses it only while |scale*log2(e)| <= 0.25 (1/sqrt(D)
+// for D >= 34), and the exact fp32 scaling otherwise.
 #include <type_traits>
 
 #include "pv_device.h"
 
 namespace pv {
 
-template <typename T>
+template <typename T, bool PRE>
 __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     const WorkItem *__restrict__ items, const uint16_t *__restrict__ q,
     const uint16_t *__restrict__ k_pages, const uint16_t *__restrict__ v_pages,
@@ -49,7 +62,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     constexpr int STAGES = 8;
     constexpr int PF = 6;                       // blocks the copies run ahead of their use
     constexpr int LOADS = STAGE_BYTES / 1024 / 4;  // 1 KiB copies per wavefront per block
-    typedef typename T::vec8 vec8;
+    static_assert(LOADS == 4, "piece layout below assumes four pieces per wavefront");
     __shared__ __attribute__((aligned(16))) unsigned char smem[STAGES][STAGE_BYTES];
 
     const WorkItem it = items[blockIdx.x];
@@ -57,6 +70,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     const int w = wave_id();
     const int q32 = lane & 31;
     const int h = lane >> 5;
+    // what multiplies a matrix-core score to get the exponent: with PRE the scores come out scaled
+    const float cfac = PRE ? 1.f : scale_log2e;
 
     // every row of the item exists (the plan only makes full 256-row items for this kernel)
     int tok[SUB], hq[SUB], vis_end[SUB];
@@ -75,17 +90,36 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     int wave_end = it.ctx + (first_row + 32 * SUB - 1) / group + 1;
     if (wave_end > it.kv_end) wave_end = it.kv_end;
 
-    vec8 qf[SUB][KS];
+    u32x4 qf[SUB][KS];  // live in accumulation registers: only the matrix cores read them
 #pragma unroll
     for (int u = 0; u < SUB; ++u) {
         const uint16_t *qrow = q + ((int64_t)(it.q_row0 + tok[u]) * num_q_heads + hq[u]) * D;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             u32x4 raw = load16(qrow + 16 * ks + 8 * h);
-            raw ^= q_sign;  // a negative scale is applied as |scale| on negated queries
-            qf[u][ks] = as_vec8<T>(raw);
+            if constexpr (PRE) {
+                // q * scale*log2(e), rounded to the 16-bit type (the sign of the scale included)
+                const typename T::vec8 v = as_vec8<T>(raw);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    raw[e] = T::pack2((float)v[2 * e] * scale_log2e,
+                                      (float)v[2 * e + 1] * scale_log2e);
+            } else {
+                raw ^= q_sign;  // a negative scale is applied as |scale| on negated queries
+            }
+            qf[u][ks] = raw;
         }
     }
+
+    // an empty statement that names every Q operand as an accumulation-register input: all of Q
+    // is in such registers, whole, wherever this stands, which keeps the register allocator from
+    // parking pieces elsewhere and shuffling them into place in front of each use
+    auto pin_q = [&]() {
+        asm volatile("" ::"a"(qf[0][0]), "a"(qf[0][1]), "a"(qf[0][2]), "a"(qf[0][3]),
+                     "a"(qf[0][4]), "a"(qf[0][5]), "a"(qf[0][6]), "a"(qf[0][7]), "a"(qf[1][0]),
+                     "a"(qf[1][1]), "a"(qf[1][2]), "a"(qf[1][3]), "a"(qf[1][4]), "a"(qf[1][5]),
+                     "a"(qf[1][6]), "a"(qf[1][7]));
+    };
 
     // LDS byte offsets of this lane's operands inside a stage (see attn_wide_kernel): S^T row i of
     // the K operand is fed with key pi(i) (bits 2 and 3 of i swapped), so that the accumulator
@@ -98,8 +132,6 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     const int last_pg = (it.kv_end - 1) >> 4;
     const int pg0 = it.kv_begin >> 4;
     const int nblocks = (it.kv_end - it.kv_begin + BK - 1) / BK;
-    const int64_t head_off = (int64_t)it.kv_head * (16 * D);
-    const int64_t page_stride = (int64_t)num_kv_heads * (16 * D);
     const uint32_t lane_bytes = (uint32_t)lane * 16u;
 
     // page ids of a block (two pages; a page past the end is never used, so any valid id will do)
@@ -108,19 +140,22 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         id0 = pt[pg <= last_pg ? pg : last_pg];
         id1 = pt[pg + 1 <= last_pg ? pg + 1 : last_pg];
     };
-    // asynchronous copy of block b into stage b % STAGES: the stage is 16 pieces of 1 KiB (K page
-    // 0, K page 1, V page 0, V page 1, four pieces each); wavefront w moves pieces w, w+4, w+8, w+12
+    // Asynchronous copy of block b into stage b % STAGES.  The stage is 16 pieces of 1 KiB: K page
+    // 0, K page 1, V page 0, V page 1, four pieces each; wavefront w moves piece w of each, i.e. the
+    // bytes [w KiB, w KiB + 1 KiB) of the (page, head) tile: source = pool + page id * page bytes
+    // + a per-wavefront constant (one 32x32 -> 64 bit multiply per page, one 64-bit add per piece).
+    const uint32_t page_bytes = (uint32_t)num_kv_heads * TILE_BYTES;
+    const uint64_t wave_off = (uint64_t)it.kv_head * TILE_BYTES + (uint32_t)w * 1024u;
+    const unsigned char *k_src = reinterpret_cast<const unsigned char *>(k_pages) + wave_off;
+    const unsigned char *v_src = reinterpret_cast<const unsigned char *>(v_pages) + wave_off;
+    auto dma_piece = [&](int b, int id0, int id1, int i) {
+        unsigned char *dst = smem[b % STAGES] + (w + 4 * i) * 1024;
+        const uint64_t page_off = (uint64_t)(uint32_t)((i & 1) ? id1 : id0) * page_bytes;
+        lds_dma16(((i & 2) ? v_src : k_src) + page_off, lane_bytes, dst);
+    };
     auto dma_block = [&](int b, int id0, int id1) {
-        unsigned char *stage = smem[b % STAGES];
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
-            const int off = (w + 4 * i) * 1024;  // wavefront-uniform offset inside the stage
-            const bool is_v = off >= HALF_BYTES;
-            const int hoff = off % HALF_BYTES;
-            const int page = hoff / TILE_BYTES ? id1 : id0;
-            const int64_t elem = (int64_t)page * page_stride + head_off + (hoff % TILE_BYTES) / 2;
-            lds_dma16((is_v ? v_pages : k_pages) + elem, lane_bytes, stage + off);
-        }
+        for (int i = 0; i < LOADS; ++i) dma_piece(b, id0, id1, i);
     };
 
     f32x16 o[SUB][NB];
@@ -130,13 +165,20 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         for (int blk = 0; blk < NB; ++blk)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[u][blk][v] = 0.f;
-    float m_run[SUB], l_run[SUB], mc[SUB];
+    // Softmax state per sub-tile.  Scores are raw matrix-core results; x = score * cfac is the
+    // exponent in the exp2 domain.  Lazy reference maximum (exact, softmax is shift-invariant): it
+    // only moves when a score of the coming block exceeds it by more than 2^kLazyLog2 in the exp2
+    // domain (thr = reference + that margin in score units; -inf while there is no reference), so
+    // rescaling the accumulators is rare.
+    float m_run[SUB], l_run[SUB], mc[SUB], thr[SUB];
 #pragma unroll
     for (int u = 0; u < SUB; ++u) {
-        m_run[u] = -INFINITY;  // reference maximum of the RAW scores (before scaling)
+        m_run[u] = -INFINITY;  // reference maximum of the scores
         l_run[u] = 0.f;        // this lane's share of the running sum
         mc[u] = 0.f;           // m_run in the exp2 domain (0 while there is no reference yet)
+        thr[u] = -INFINITY;
     }
+    const float lazy_margin = kLazyLog2 / cfac;  // +inf for a zero scale: set once, kept
 
     u32x4 kf[KS];  // K operands of the block whose scores are computed next
     auto read_k = [&](int b) {
@@ -145,23 +187,46 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         for (int ks = 0; ks < KS; ++ks)
             kf[ks] = *reinterpret_cast<const u32x4 *>(sb + k_lds + ks * 512);
     };
-    // S^T of the block whose K operands are in kf, both sub-tiles (they share the operands)
+    // S^T of the block whose K operands are in kf, both sub-tiles (they share the operands), for
+    // the prologue and the masked loop.  Every use of the Q operands in this kernel is a pinned
+    // instruction with the operand in an accumulation register, so that the register allocator
+    // keeps all of Q there for good.  Outside the hand-laid schedule of the pipelined loop the
+    // compiler may still move an operand into place right in front of the statement, hence the
+    // guarded form here, and the wait for the results before anything reads them.
     auto scores = [&](f32x16 (&sn)[SUB]) {
 #pragma unroll
-        for (int u = 0; u < SUB; ++u)
+        for (int u = 0; u < SUB; ++u) T::mfma32_first_guarded(sn[u], kf[0], qf[u][0]);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) sn[u][v] = 0.f;
+        for (int ks = 1; ks < KS; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int u = 0; u < SUB; ++u) sn[u] = T::mfma32(as_vec8<T>(kf[ks]), qf[u][ks], sn[u]);
+            for (int u = 0; u < SUB; ++u) T::mfma32_next_guarded(sn[u], kf[ks], qf[u][ks]);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
     };
     // register v = 8*page + j of S^T  <->  key kb0 + 16*page + 8*h + j
     auto key_of = [&](int kb0, int v) { return kb0 + 16 * (v >> 3) + 8 * h + (v & 7); };
 
-    // Lazy reference maximum (exact, softmax is shift-invariant): it only moves when a score of
-    // the coming block exceeds it by more than 2^kLazyLog2 in the scaled domain, so rescaling the
-    // accumulators is rare.  Works on the scores of the block that the NEXT softmax will consume.
+    // moves the reference of every row whose block maximum mx (score units) exceeds its threshold
+    auto raise_reference = [&](const float (&mx)[SUB]) {
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            const float mxx = fmaxf(mx[u], __shfl_xor(mx[u], 32));
+            const float m_new = mxx > thr[u] ? mxx : m_run[u];
+            const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha =
+                m_run[u] == -INFINITY ? 0.f : fast_exp2((m_run[u] - m_safe) * cfac);
+            mc[u] = m_safe * cfac;
+            m_run[u] = m_new;
+            thr[u] = m_new == -INFINITY ? -INFINITY : m_new + lazy_margin;
+            l_run[u] *= alpha;
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int blk = 0; blk < NB; ++blk) o[u][blk] *= alpha;
+            }
+        }
+    };
+    // works on the scores of the block that the NEXT softmax will consume
     auto update_reference = [&](const f32x16 (&sn)[SUB], int kb0, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         float mx[SUB];
@@ -176,28 +241,9 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                     if (key_of(kb0, v) >= vis_end[u]) x = -INFINITY;
                 mx[u] = fmaxf(mx[u], x);
             }
-            grow = grow || m_run[u] == -INFINITY || (mx[u] - m_run[u]) * scale_log2e > kLazyLog2;
+            grow = grow || mx[u] > thr[u];
         }
-        if (__any(grow)) {
-#pragma unroll
-            for (int u = 0; u < SUB; ++u) {
-                const float mxx = fmaxf(mx[u], __shfl_xor(mx[u], 32));
-                const float m_new = (m_run[u] == -INFINITY ||
-                                     (mxx - m_run[u]) * scale_log2e > kLazyLog2)
-                                        ? mxx
-                                        : m_run[u];
-                const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha =
-                    m_run[u] == -INFINITY ? 0.f : fast_exp2((m_run[u] - m_safe) * scale_log2e);
-                mc[u] = m_safe * scale_log2e;
-                m_run[u] = m_new;
-                l_run[u] *= alpha;
-                if (__any(alpha != 1.f)) {
-#pragma unroll
-                    for (int blk = 0; blk < NB; ++blk) o[u][blk] *= alpha;
-                }
-            }
-        }
+        if (__any(grow)) raise_reference(mx);
     };
 
     // exponentials of block b (scores in s) and O^T += V^T P^T for both sub-tiles
@@ -213,8 +259,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) {
                     const int v = 8 * pg + 2 * jj;
-                    float p0 = fast_exp2(__builtin_fmaf(s[u][v], scale_log2e, -mc[u]));
-                    float p1 = fast_exp2(__builtin_fmaf(s[u][v + 1], scale_log2e, -mc[u]));
+                    float p0 = fast_exp2(__builtin_fmaf(s[u][v], cfac, -mc[u]));
+                    float p1 = fast_exp2(__builtin_fmaf(s[u][v + 1], cfac, -mc[u]));
                     if constexpr (MASKED) {
                         p0 = key_of(kb0, v) < vis_end[u] ? p0 : 0.f;
                         p1 = key_of(kb0, v + 1) < vis_end[u] ? p1 : 0.f;
@@ -248,11 +294,11 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     // end of iteration b: the copies of block b+3 (issued three iterations ago) must have landed
     // before the barrier publishes them; younger copies may stay in flight.  This wavefront's LDS
     // reads of block b have been consumed by then, so after the barrier stage b % STAGES may be
-    // refilled (it is, two iterations later).
-    auto publish = [&](int b) {
+    // refilled (it is, two iterations later).  `more` = a copy was issued in this iteration.
+    auto publish = [&](bool more) {
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("" ::: "memory");
-        if (b + PF < nblocks)
+        if (more)
             __builtin_amdgcn_s_waitcnt(waitcnt_imm((PF - 3) * LOADS, 15));
         else
             __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
@@ -267,13 +313,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         dma_block(b, id0, id1);
     }
     page_ids(PF, id0, id1);
-    asm volatile("" ::: "memory");
-    if (nblocks > PF)
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm((PF - 3) * LOADS, 15));
-    else
-        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    publish(nblocks > PF);
 
     f32x16 s[SUB], sn[SUB];
     read_k(0);
@@ -281,28 +321,183 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     update_reference(s, it.kv_begin, std::true_type{});
     read_k(1);  // a stage without a block holds stale data: those scores are never used
 
-    // blocks 0 .. nfast are unmasked for every row of this wavefront
+    // One pipelined iteration: block b's exponents (PRE) or scores are in `cur`; leaves those of
+    // block b+1 in `nxt`.  With PRE an "exponent" is score - reference, ready for exp2: the score
+    // product starts from cinit = -reference instead of zero.  The instruction order is laid out
+    // by hand in 32 slots, one matrix-core instruction each, fenced so that the compiler keeps it:
+    //   slots  0-15  score product of block b+1 (k-step slot/2, sub-tile slot%2), and the
+    //                exponentials of block b as a pipeline over its 16 score pairs (scale-and-shift
+    //                unless PRE, exp2 one slot later, pack to 16 bits one slot after that);
+    //   slots 16-31  value product of block b (V operand (slot-16)/2, sub-tile slot%2; every P
+    //                operand is complete when its instruction issues), the V operands requested
+    //                six slots ahead of their use; in between the copy of block b+PF (slots 16-19), the
+    //                page ids of the next copy, from slot 20 on the maximum of block b+1's results
+    //                (its last score instruction issued in slot 15, see mfma32_first); K operands
+    //                are requested six slots ahead of their use as well, those of the next
+    //                iteration's first three k-steps in slots 26-30;
+    //   then the sixteen row-sum dot products in one cluster, the test for a reference update,
+    //   and the barrier.
+    f32x16 cinit[SUB];
+    float thr_rel[SUB];  // PRE: threshold for block maxima that are relative to the reference
+    auto fast_step = [&](int b, const f32x16 (&cur)[SUB], f32x16 (&nxt)[SUB]) {
+        pin_q();
+        const unsigned char *sb = smem[b % STAGES];
+        const unsigned char *sk1 = smem[(b + 1) % STAGES];
+        const unsigned char *sk = smem[(b + 2) % STAGES];
+        u32x4 vf[2][NB];
+        u32x4 praw[SUB][2];
+        float xs[SUB * 8][2], es[SUB * 8][2];
+        float mx[SUB];
+#pragma unroll
+        for (int slot = 0; slot < 32; ++slot) {
+            // --- the slot's matrix-core instruction
+            if (slot < 16) {
+                const int ks = slot / 2, u = slot % 2;
+                if (ks == 0) {
+                    if constexpr (PRE)
+                        T::mfma32_from(nxt[u], kf[0], qf[u][0], cinit[u]);
+                    else
+                        T::mfma32_first(nxt[u], kf[0], qf[u][0]);
+                } else {
+                    T::mfma32_next(nxt[u], kf[ks], qf[u][ks]);
+                }
+            } else {
+                // V operand i = 4*page + blk feeds both sub-tiles back to back, so it is live
+                // for a few slots only
+                const int i = (slot - 16) / 2, u = (slot - 16) % 2;
+                const int pg = i / 4, blk = i % 4;
+                o[u][blk] = T::mfma32(as_vec8<T>(vf[pg][blk]), as_vec8<T>(praw[u][pg]), o[u][blk]);
+            }
+            // --- LDS reads: V operand i of this block six slots ahead of its first use (they
+            //     take over the registers of K operands already consumed), later the K operands
+            //     of block b+2
+            if (slot >= 10 && slot < 26 && slot % 2 == 0) {
+                const int i = (slot - 10) / 2;
+                vf[i / 4][i % 4] = *reinterpret_cast<const u32x4 *>(
+                    sb + v_lds + (i / 4) * TILE_BYTES + (i % 4) * 512);
+            }
+            // K operand ks of block b+1 is used in slots 2*ks, 2*ks+1: operands 3-7 are requested
+            // six slots ahead, operands 0-2 of block b+2 at the end (slots 26, 28, 30)
+            if (slot <= 8 && slot % 2 == 0)
+                kf[3 + slot / 2] =
+                    *reinterpret_cast<const u32x4 *>(sk1 + k_lds + (3 + slot / 2) * 512);
+            if (slot >= 26 && slot % 2 == 0)
+                kf[(slot - 26) / 2] =
+                    *reinterpret_cast<const u32x4 *>(sk + k_lds + ((slot - 26) / 2) * 512);
+            // --- exponentials: pair j = 8*u + 4*page + jj holds results 2*(j%8), 2*(j%8)+1 of u
+            if constexpr (PRE) {
+                if (slot < 16) {
+                    const int u = slot / 8, v = 2 * (slot % 8);
+                    es[slot][0] = fast_exp2(cur[u][v]);
+                    es[slot][1] = fast_exp2(cur[u][v + 1]);
+                }
+                if (slot >= 1 && slot < 17) {
+                    const int j = slot - 1;
+                    praw[j / 8][(j % 8) / 4][j % 4] = T::pack2(es[j][0], es[j][1]);
+                }
+            } else {
+                if (slot < 16) {
+                    const int u = slot / 8, v = 2 * (slot % 8);
+                    xs[slot][0] = __builtin_fmaf(cur[u][v], cfac, -mc[u]);
+                    xs[slot][1] = __builtin_fmaf(cur[u][v + 1], cfac, -mc[u]);
+                }
+                if (slot >= 1 && slot < 17) {
+                    es[slot - 1][0] = fast_exp2(xs[slot - 1][0]);
+                    es[slot - 1][1] = fast_exp2(xs[slot - 1][1]);
+                }
+                if (slot >= 2 && slot < 18) {
+                    const int j = slot - 2;
+                    praw[j / 8][(j % 8) / 4][j % 4] = T::pack2(es[j][0], es[j][1]);
+                }
+            }
+            // --- copy of block b+PF (b + PF < nblocks inside the pipelined loop), one piece a slot
+            if (slot >= 16 && slot < 16 + LOADS) dma_piece(b + PF, id0, id1, slot - 16);
+            if (slot == 16 + LOADS) page_ids(b + PF + 1, id0, id1);
+            // --- maximum of block b+1's results, two registers per slot and sub-tile
+            if (slot >= 20 && slot < 28) {
+                const int i = slot - 20;
+#pragma unroll
+                for (int u = 0; u < SUB; ++u)
+                    mx[u] = max3_raw(i == 0 ? nxt[u][0] : mx[u], nxt[u][2 * i], nxt[u][2 * i + 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // --- row sums of what the matrix cores saw, in one cluster
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            float psum = 0.f;
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) psum = T::add_pair(praw[u][pg][jj], psum);
+            l_run[u] += psum;
+        }
+        if constexpr (PRE) {
+            if (__any(mx[0] > thr_rel[0] || mx[1] > thr_rel[1])) {
+                float mx_abs[SUB], mc_old[SUB];
+#pragma unroll
+                for (int u = 0; u < SUB; ++u) {
+                    mc_old[u] = mc[u];
+                    mx_abs[u] = mx[u] + mc[u];  // cfac = 1: scores and exponents share a unit
+                }
+                raise_reference(mx_abs);
+#pragma unroll
+                for (int u = 0; u < SUB; ++u) {
+                    const float shift = mc_old[u] - mc[u];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        nxt[u][v] += shift;  // block b+1's exponents follow the new reference
+                        cinit[u][v] = -mc[u];
+                    }
+                    thr_rel[u] = thr[u] - mc[u];
+                }
+                asm volatile("s_nop 1" ::: "memory");  // cinit feeds a pinned instruction soon
+            }
+        } else {
+            if (__any(mx[0] > thr[0] || mx[1] > thr[1])) raise_reference(mx);
+        }
+        publish(true);
+    };
+
+    // blocks 0 .. nfast are unmasked for every row of this wavefront, and every pipelined
+    // iteration still has a copy to issue
     int nfast = (unmasked_end - it.kv_begin) / BK - 1;
-    if (nfast > nblocks - 1) nfast = nblocks - 1;
+    if (nfast > nblocks - PF) nfast = nblocks - PF;
     if (nfast < 0) nfast = 0;
+    nfast &= ~1;  // pairs: the results ping-pong between two register sets without copies
 
     int b = 0;
     // ---- pipelined loop over unmasked blocks that have an unmasked successor ----
-    for (; b < nfast; ++b) {
-        if (b + PF < nblocks) dma_block(b + PF, id0, id1);
-        page_ids(b + PF + 1, id0, id1);
-        const int kb0 = it.kv_begin + BK * b;
-        scores(sn);                                                  // block b+1
-        softmax_pv(s, smem[b % STAGES], kb0, std::false_type{});     // block b
-        read_k(b + 2);
-        update_reference(sn, kb0 + BK, std::false_type{});
+    if (nfast > 0) {
+        if constexpr (PRE) {
+            // scores -> exponents for the block in flight, and the starting value of the next ones
 #pragma unroll
-        for (int u = 0; u < SUB; ++u) s[u] = sn[u];
-        publish(b);
+            for (int u = 0; u < SUB; ++u) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    s[u][v] -= mc[u];
+                    cinit[u][v] = -mc[u];
+                }
+                thr_rel[u] = thr[u] - mc[u];
+            }
+            asm volatile("s_nop 1" ::: "memory");  // cinit feeds a pinned instruction next
+        }
+        for (; b < nfast; b += 2) {
+            fast_step(b, s, sn);
+            fast_step(b + 1, sn, s);
+        }
+        if constexpr (PRE) {  // back to scores for the masked loop
+#pragma unroll
+            for (int u = 0; u < SUB; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[u][v] += mc[u];
+        }
+        read_k(b + 1);  // the pipelined loop had requested the first three operands only
     }
     // ---- masked loop: blocks at the causal boundary / the end of the sequence ----
     for (; b < nblocks; ++b) {
-        if (b + PF < nblocks) dma_block(b + PF, id0, id1);
+        const bool more = b + PF < nblocks;
+        if (more) dma_block(b + PF, id0, id1);
         page_ids(b + PF + 1, id0, id1);
         const int kb0 = it.kv_begin + BK * b;
         if (kb0 < wave_end) softmax_pv(s, smem[b % STAGES], kb0, std::true_type{});
@@ -311,7 +506,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
             update_reference(s, kb0 + BK, std::true_type{});
         }
         read_k(b + 2);
-        publish(b);
+        publish(more);
     }
 
     // ---- finish: every lane owns one row per sub-tile; the two half-waves hold partial sums ----
@@ -344,7 +539,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                 }
             if (h == 0) {
                 // the merge works in the log2 domain of the scaled scores
-                ws_ml[2 * slot] = m_run[u] == -INFINITY ? -INFINITY : m_run[u] * scale_log2e;
+                ws_ml[2 * slot] = m_run[u] == -INFINITY ? -INFINITY : m_run[u] * cfac;
                 ws_ml[2 * slot + 1] = l_tot;
             }
         }
@@ -357,13 +552,23 @@ static hipError_t launch_tile256_t(const pv_plan *plan, const void *q, const voi
                                    void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
     const int n = (int)plan->tile256.size();
-    const float c = (scale < 0.f ? -scale : scale) * kLog2e;
-    const uint32_t q_sign = scale < 0.f ? 0x80008000u : 0u;
-    hipLaunchKernelGGL((attn_tile256_kernel<T>), dim3(n), dim3(256), 0, stream, plan->d_tile256,
-                       (const uint16_t *)q, (const uint16_t *)k_pages, (const uint16_t *)v_pages,
-                       page_table, plan->max_pages_per_req, plan->num_q_heads,
-                       plan->pool.num_kv_heads, plan->group, c, q_sign, (uint16_t *)out, ws_o,
-                       ws_ml);
+    const float c_signed = scale * kLog2e;
+    const float c_abs = c_signed < 0.f ? -c_signed : c_signed;
+    if (c_abs <= 0.25f) {
+        // queries pre-multiplied by scale*log2(e): the sign travels with them
+        hipLaunchKernelGGL((attn_tile256_kernel<T, true>), dim3(n), dim3(256), 0, stream,
+                           plan->d_tile256, (const uint16_t *)q, (const uint16_t *)k_pages,
+                           (const uint16_t *)v_pages, page_table, plan->max_pages_per_req,
+                           plan->num_q_heads, plan->pool.num_kv_heads, plan->group, c_signed, 0u,
+                           (uint16_t *)out, ws_o, ws_ml);
+    } else {
+        const uint32_t q_sign = scale < 0.f ? 0x80008000u : 0u;
+        hipLaunchKernelGGL((attn_tile256_kernel<T, false>), dim3(n), dim3(256), 0, stream,
+                           plan->d_tile256, (const uint16_t *)q, (const uint16_t *)k_pages,
+                           (const uint16_t *)v_pages, page_table, plan->max_pages_per_req,
+                           plan->num_q_heads, plan->pool.num_kv_heads, plan->group, c_abs, q_sign,
+                           (uint16_t *)out, ws_o, ws_ml);
+    }
     return hipGetLastError();
 }
 

@@ -29,6 +29,37 @@ struct F16 {
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
+    // The same instruction with its registers pinned: result in ordinary vector registers (the
+    // vector ALU reads it next), A operand in vector registers, B operand in accumulation
+    // registers (operands that stay put for the whole kernel).  The compiler does not know what
+    // the statement is: whoever reads `d` must keep the instruction's latency in mind (at least
+    // two further matrix-core instructions, or the equivalent in s_nop, before a vector-ALU read).
+    static __device__ __forceinline__ void mfma32_first(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b_acc));
+    }
+    // d = a * b + c with c in other registers than d
+    static __device__ __forceinline__ void mfma32_from(f32x16 &d, u32x4 a, u32x4 b_acc, f32x16 c)
+    {
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3"
+                     : "=&v"(d) : "v"(a), "a"(b_acc), "v"(c));
+    }
+    static __device__ __forceinline__ void mfma32_next(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b_acc));
+    }
+    // the same two with the wait states a vector-ALU write of an operand needs in front: for code
+    // outside hand-laid schedules, where the compiler may move operands into place at the last moment
+    static __device__ __forceinline__ void mfma32_first_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, 0"
+                     : "=&v"(d) : "v"(a), "a"(b_acc));
+    }
+    static __device__ __forceinline__ void mfma32_next_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0"
+                     : "+v"(d) : "v"(a), "a"(b_acc));
+    }
     // two fp32 -> one dword of two 16-bit values (round to nearest even), low half first
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     {
@@ -54,6 +85,32 @@ struct BF16 {
     static __device__ __forceinline__ f32x16 mfma32(vec8 a, vec8 b, f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void mfma32_first(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b_acc));
+    }
+    // d = a * b + c with c in other registers than d
+    static __device__ __forceinline__ void mfma32_from(f32x16 &d, u32x4 a, u32x4 b_acc, f32x16 c)
+    {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3"
+                     : "=&v"(d) : "v"(a), "a"(b_acc), "v"(c));
+    }
+    static __device__ __forceinline__ void mfma32_next(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b_acc));
+    }
+    // the same two with the wait states a vector-ALU write of an operand needs in front: for code
+    // outside hand-laid schedules, where the compiler may move operands into place at the last moment
+    static __device__ __forceinline__ void mfma32_first_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
+                     : "=&v"(d) : "v"(a), "a"(b_acc));
+    }
+    static __device__ __forceinline__ void mfma32_next_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    {
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+                     : "+v"(d) : "v"(a), "a"(b_acc));
     }
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     {
@@ -87,6 +144,15 @@ __device__ __forceinline__ u32x4 load16_stream(const void *p)
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max(a, b, c) in one instruction, for values that are known not to be signalling NaNs (fmaxf on
+// values the compiler cannot see through costs an extra canonicalising instruction per input)
+__device__ __forceinline__ float max3_raw(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
 
 // lane index of the calling thread within its wavefront, wave index made scalar
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63u); }
