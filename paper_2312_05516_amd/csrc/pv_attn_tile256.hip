@@ -64,6 +64,10 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     constexpr int LOADS = STAGE_BYTES / 1024 / 4;  // 1 KiB copies per wavefront per block
     static_assert(LOADS == 4, "piece layout below assumes four pieces per wavefront");
     __shared__ __attribute__((aligned(16))) unsigned char smem[STAGES][STAGE_BYTES];
+    // the item's page ids, two per block: read back through LDS, whose results return in order
+    // with the operand reads (a scalar load in the loop would make every wait for an operand a
+    // wait for that load too)
+    __shared__ __attribute__((aligned(8))) int32_t page_lds[kTileMaxPages];
 
     const WorkItem it = items[blockIdx.x];
     const int lane = lane_id();
@@ -111,16 +115,6 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         }
     }
 
-    // an empty statement that names every Q operand as an accumulation-register input: all of Q
-    // is in such registers, whole, wherever this stands, which keeps the register allocator from
-    // parking pieces elsewhere and shuffling them into place in front of each use
-    auto pin_q = [&]() {
-        asm volatile("" ::"a"(qf[0][0]), "a"(qf[0][1]), "a"(qf[0][2]), "a"(qf[0][3]),
-                     "a"(qf[0][4]), "a"(qf[0][5]), "a"(qf[0][6]), "a"(qf[0][7]), "a"(qf[1][0]),
-                     "a"(qf[1][1]), "a"(qf[1][2]), "a"(qf[1][3]), "a"(qf[1][4]), "a"(qf[1][5]),
-                     "a"(qf[1][6]), "a"(qf[1][7]));
-    };
-
     // LDS byte offsets of this lane's operands inside a stage (see attn_wide_kernel): S^T row i of
     // the K operand is fed with key pi(i) (bits 2 and 3 of i swapped), so that the accumulator
     // registers of S^T, in order, are the 8 consecutive keys the P^T operand needs.
@@ -135,10 +129,14 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     const uint32_t lane_bytes = (uint32_t)lane * 16u;
 
     // page ids of a block (two pages; a page past the end is never used, so any valid id will do)
+    for (int i = (int)threadIdx.x; i < 2 * nblocks && i < kTileMaxPages; i += 256)
+        page_lds[i] = pt[pg0 + i <= last_pg ? pg0 + i : last_pg];
+    __syncthreads();
     auto page_ids = [&](int b, int &id0, int &id1) {
-        const int pg = pg0 + 2 * b;
-        id0 = pt[pg <= last_pg ? pg : last_pg];
-        id1 = pt[pg + 1 <= last_pg ? pg + 1 : last_pg];
+        const int bb = b < nblocks ? b : nblocks - 1;  // ids past the last block are never used
+        const u32x2 ids = *reinterpret_cast<const u32x2 *>(&page_lds[2 * bb]);
+        id0 = __builtin_amdgcn_readfirstlane((int)ids[0]);
+        id1 = __builtin_amdgcn_readfirstlane((int)ids[1]);
     };
     // Asynchronous copy of block b into stage b % STAGES.  The stage is 16 pieces of 1 KiB: K page
     // 0, K page 1, V page 0, V page 1, four pieces each; wavefront w moves piece w of each, i.e. the
@@ -189,8 +187,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     };
     // S^T of the block whose K operands are in kf, both sub-tiles (they share the operands), for
     // the prologue and the masked loop.  Every use of the Q operands in this kernel is a pinned
-    // instruction with the operand in an accumulation register, so that the register allocator
-    // keeps all of Q there for good.  Outside the hand-laid schedule of the pipelined loop the
+    // instruction with the operand in an accumulation register (see mfma32_first), so that the
+    // register allocator keeps all of Q there for good.  Outside the hand-laid schedule of the pipelined loop the
     // compiler may still move an operand into place right in front of the statement, hence the
     // guarded form here, and the wait for the results before anything reads them.
     auto scores = [&](f32x16 (&sn)[SUB]) {
@@ -340,7 +338,6 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     f32x16 cinit[SUB];
     float thr_rel[SUB];  // PRE: threshold for block maxima that are relative to the reference
     auto fast_step = [&](int b, const f32x16 (&cur)[SUB], f32x16 (&nxt)[SUB]) {
-        pin_q();
         const unsigned char *sb = smem[b % STAGES];
         const unsigned char *sk1 = smem[(b + 1) % STAGES];
         const unsigned char *sk = smem[(b + 2) % STAGES];
@@ -578,6 +575,10 @@ hipError_t launch_attn_tile256(const pv_plan *plan, const void *q, const void *k
 {
     if (plan->tile256.empty()) return hipSuccess;
     if (plan->pool.head_dim != 128) return hipErrorInvalidValue;  // the plan never does this
+    for (const WorkItem &w : plan->tile256)  // what the kernel assumes of its items
+        if (w.row_count != kTileRows || w.kv_end <= w.kv_begin || w.kv_begin % kKvBlock != 0 ||
+            (int64_t)w.kv_end - w.kv_begin > (int64_t)kTileMaxPages * 16)
+            return hipErrorInvalidValue;
     return plan->pool.dtype == PV_F16
                ? launch_tile256_t<F16>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                        ws_ml, stream)

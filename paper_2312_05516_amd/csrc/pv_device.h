@@ -31,34 +31,36 @@ struct F16 {
     }
     // The same instruction with its registers pinned: result in ordinary vector registers (the
     // vector ALU reads it next), A operand in vector registers, B operand in accumulation
-    // registers (operands that stay put for the whole kernel).  The compiler does not know what
+    // registers (operands that stay put for the whole kernel; named as read-write, though the
+    // instruction only reads them, so that the value stays in that register from use to use
+    // instead of being parked elsewhere and moved into place).  The compiler does not know what
     // the statement is: whoever reads `d` must keep the instruction's latency in mind (at least
     // two further matrix-core instructions, or the equivalent in s_nop, before a vector-ALU read).
-    static __device__ __forceinline__ void mfma32_first(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_first(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %2, %1, 0" : "=&v"(d), "+a"(b_acc) : "v"(a));
     }
     // d = a * b + c with c in other registers than d
-    static __device__ __forceinline__ void mfma32_from(f32x16 &d, u32x4 a, u32x4 b_acc, f32x16 c)
+    static __device__ __forceinline__ void mfma32_from(f32x16 &d, u32x4 a, u32x4 &b_acc, f32x16 c)
     {
-        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3"
-                     : "=&v"(d) : "v"(a), "a"(b_acc), "v"(c));
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %2, %1, %3"
+                     : "=&v"(d), "+a"(b_acc) : "v"(a), "v"(c));
     }
-    static __device__ __forceinline__ void mfma32_next(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_next(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("v_mfma_f32_32x32x16_f16 %0, %2, %1, %0" : "+v"(d), "+a"(b_acc) : "v"(a));
     }
     // the same two with the wait states a vector-ALU write of an operand needs in front: for code
     // outside hand-laid schedules, where the compiler may move operands into place at the last moment
-    static __device__ __forceinline__ void mfma32_first_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_first_guarded(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, 0"
-                     : "=&v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %2, %1, 0"
+                     : "=&v"(d), "+a"(b_acc) : "v"(a));
     }
-    static __device__ __forceinline__ void mfma32_next_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_next_guarded(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0"
-                     : "+v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %2, %1, %0"
+                     : "+v"(d), "+a"(b_acc) : "v"(a));
     }
     // two fp32 -> one dword of two 16-bit values (round to nearest even), low half first
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
@@ -86,31 +88,31 @@ struct BF16 {
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
-    static __device__ __forceinline__ void mfma32_first(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_first(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %2, %1, 0" : "=&v"(d), "+a"(b_acc) : "v"(a));
     }
     // d = a * b + c with c in other registers than d
-    static __device__ __forceinline__ void mfma32_from(f32x16 &d, u32x4 a, u32x4 b_acc, f32x16 c)
+    static __device__ __forceinline__ void mfma32_from(f32x16 &d, u32x4 a, u32x4 &b_acc, f32x16 c)
     {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3"
-                     : "=&v"(d) : "v"(a), "a"(b_acc), "v"(c));
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %2, %1, %3"
+                     : "=&v"(d), "+a"(b_acc) : "v"(a), "v"(c));
     }
-    static __device__ __forceinline__ void mfma32_next(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_next(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(d), "+a"(b_acc) : "v"(a));
     }
     // the same two with the wait states a vector-ALU write of an operand needs in front: for code
     // outside hand-laid schedules, where the compiler may move operands into place at the last moment
-    static __device__ __forceinline__ void mfma32_first_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_first_guarded(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
-                     : "=&v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, 0"
+                     : "=&v"(d), "+a"(b_acc) : "v"(a));
     }
-    static __device__ __forceinline__ void mfma32_next_guarded(f32x16 &d, u32x4 a, u32x4 b_acc)
+    static __device__ __forceinline__ void mfma32_next_guarded(f32x16 &d, u32x4 a, u32x4 &b_acc)
     {
-        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
-                     : "+v"(d) : "v"(a), "a"(b_acc));
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, %0"
+                     : "+v"(d), "+a"(b_acc) : "v"(a));
     }
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
     {

@@ -75,8 +75,9 @@ static int64_t item_cost(const WorkItem &w, int rows_per_step)
 //    item longer than `chunk` into parts of about that length;
 //  * in a longer list only the outliers are cut, items more than twice as long as `chunk`, because
 //    one workgroup walking such an item alone would outlast everything else.
+//  * whatever the list, no part is longer than max_len keys (0 = no such limit).
 static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &combine,
-                        int64_t &slots, const Tuning &tune)
+                        int64_t &slots, const Tuning &tune, int64_t max_len = 0)
 {
     if (items.empty()) return;
     int64_t total_keys = 0;
@@ -85,10 +86,11 @@ static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &
     chunk = std::max<int64_t>(chunk, tune.min_split_keys);
     chunk = (chunk + kKvBlock - 1) / kKvBlock * kKvBlock;
     const bool outliers_only = (int64_t)items.size() >= tune.split_target;
+    auto too_long = [&](int64_t len) { return max_len > 0 && len > max_len; };
     auto wants_split = [&](const WorkItem &w) {
         const int64_t len = w.kv_end - w.kv_begin;
-        return len > chunk && len >= 2 * (int64_t)tune.min_split_keys &&
-               !(outliers_only && len <= 2 * chunk);
+        return too_long(len) || (len > chunk && len >= 2 * (int64_t)tune.min_split_keys &&
+                                 !(outliers_only && len <= 2 * chunk));
     };
     bool any = false;
     for (const WorkItem &w : items) any = any || wants_split(w);
@@ -99,7 +101,10 @@ static void split_items(std::vector<WorkItem> &items, std::vector<CombineItem> &
         const int64_t len = w.kv_end - w.kv_begin;
         int64_t parts = (len + chunk - 1) / chunk;
         if (parts <= 1 || len < 2 * (int64_t)tune.min_split_keys ||
-            (outliers_only && len <= 2 * chunk)) {
+            (outliers_only && len <= 2 * chunk))
+            parts = 1;
+        if (too_long(len)) parts = std::max(parts, (len + max_len - 1) / max_len);
+        if (parts <= 1) {
             result.push_back(w);
             continue;
         }
@@ -357,7 +362,8 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     int64_t slots = 0;
     split_items(plan->narrow, plan->combine, slots, tune);
     split_items(plan->wide, plan->combine, slots, tune);
-    split_items(plan->tile256, plan->combine, slots, tune);
+    split_items(plan->tile256, plan->combine, slots, tune,
+                (int64_t)kTileMaxPages * pool->page_size - kKvBlock);
     if (slots > INT32_MAX / 2) {
         delete plan;
         return PV_ERR_OUT_OF_RANGE;

@@ -61,6 +61,8 @@ constexpr int kNarrowRows = 16;  // rows per item of the bandwidth-oriented kern
 constexpr int kWideRows = 128;   // rows per item of the matrix-core kernel (4 waves x 32 rows)
 constexpr int kTileRows = 256;   // rows per item of the 256-row matrix-core kernel (4 waves x 64)
 constexpr int kKvBlock = 32;     // keys per inner step (two pages)
+constexpr int kTileMaxPages = 8192;  // page ids an item of the 256-row kernel may span (it keeps
+                                     // them in LDS): its KV range is at most 16 times that
 
 struct Tuning {
     int32_t split_target;    // aim for at least this many work items per kernel
