@@ -49,7 +49,7 @@ Tuning default_tuning()
     t.unify_max_steps = env_int("PV_UNIFY_MAX_STEPS", 90000);
     {
         const char *v = std::getenv("PV_TILE_MIN_KEYS");
-        t.tile_min_keys = (v && *v == '0' && !v[1]) ? 0 : env_int("PV_TILE_MIN_KEYS", 0);
+        t.tile_min_keys = (v && *v == '0' && !v[1]) ? 0 : env_int("PV_TILE_MIN_KEYS", 8192);
     }
     return t;
 }
