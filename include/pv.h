@@ -22,8 +22,10 @@
  *     before anything is launched.  The *contents* of device index arrays are
  *     not checked by the launching calls; pv_plan_check_page_table() checks a
  *     host copy.
+ *   - The library keeps no global state and allocates device memory in two documented places only
+ *     (pv_plan_upload; the one-shot forms when the workspace passed is too small for the lists).
  *   - A plan may be shared by the launches of many layers, but by one host thread at a time (a
- *     launch updates the plan's timing state and, the first time, uploads it).
+ *     launch updates the plan's timing state).
  *   - Alignment: q, out, k_new, v_new, the pools and the rotary table are read and written with
  *     16-byte vector accesses: every such pointer must be 16-byte aligned (the launching calls
  *     return PV_ERR_INVALID_ARG otherwise); a workspace must be 256-byte aligned.
@@ -103,22 +105,35 @@ int64_t pv_pool_v_offset(const pv_pool_desc *pool, int32_t page, int32_t head, i
  * for request r, NOT including its q_lens[r] new ones; both are host arrays of num_reqs
  * entries.  q_lens[r] == 0 is legal (the request produces nothing); num_reqs == 0 is legal.
  * Every request must fit its page-table row: ceil((ctx+q)/page_size) <= max_pages_per_req,
- * else PV_ERR_OUT_OF_RANGE.  On success *plan owns host memory (and, after the first launch
- * or pv_plan_upload, a few KB..MB of device memory) until pv_plan_destroy.
+ * else PV_ERR_OUT_OF_RANGE.  On success *plan owns host memory only, until pv_plan_destroy.
  */
 pv_status pv_plan_create(const pv_pool_desc *pool, int32_t num_q_heads,
                          const int32_t *ctx_lens /* host [num_reqs] */,
                          const int32_t *q_lens /* host [num_reqs] */, int32_t num_reqs,
                          int32_t max_pages_per_req, pv_plan **plan);
 
-/* Frees host and device memory of the plan.  The caller must make sure no launch that uses the
- * plan is still running.  NULL is ignored. */
+/* Frees the plan (and the device memory pv_plan_upload allocated, if it was used).  The caller
+ * must make sure no launch that uses the plan is still running.  NULL is ignored. */
 void pv_plan_destroy(pv_plan *plan);
 
-/* Copies the plan's arrays to the current HIP device (allocates device memory, synchronous).
- * Called implicitly by the first *_planned launch; calling it earlier keeps the allocation out
- * of the first timed launch.  Idempotent. */
+/*
+ * The kernels read the plan's lists (work items, prefix sums, append groups) from device memory.
+ * A *_planned launch never allocates or copies: the lists must have been put on the current
+ * device first, by one of the two calls below, else the launch returns PV_ERR_INVALID_ARG.
+ *
+ * pv_plan_upload_to: the caller owns the memory.  Copies pv_plan_device_bytes(plan) bytes into
+ * device_buf (256-byte aligned, at least that large, else PV_ERR_WORKSPACE) with one asynchronous
+ * copy on `stream`, allocates nothing and does not wait; launches on the same stream may follow
+ * at once.  The buffer must stay untouched until the last launch that uses the plan has finished.
+ *
+ * pv_plan_upload: convenience.  Allocates device memory that the plan then owns (freed by
+ * pv_plan_destroy), copies, and waits for the copy.  Idempotent.
+ */
+size_t pv_plan_device_bytes(const pv_plan *plan);
+pv_status pv_plan_upload_to(pv_plan *plan, void *device_buf, size_t bytes, void *stream);
 pv_status pv_plan_upload(pv_plan *plan);
+/* 1 if the plan holds device memory of its own (pv_plan_upload was used), 0 if not, -1 for NULL. */
+int32_t pv_plan_owns_device_memory(const pv_plan *plan);
 
 /* Total number of new tokens (rows of q / out / k_new / v_new). */
 int32_t pv_plan_total_q(const pv_plan *plan);
@@ -129,8 +144,10 @@ const int32_t *pv_plan_q_start(const pv_plan *plan);
 size_t pv_plan_workspace_bytes(const pv_plan *plan);
 
 /* Work-item introspection (for tests and reports).  kind: 0 = items of the bandwidth-oriented
- * kernel (at most 16 query rows per item), 1 = items of the matrix-core kernel, 2 = split-KV
- * combine items.  pv_plan_work_item fills eight int32 fields:
+ * kernel (at most 16 query rows per item), 1 = items of the matrix-core kernel (at most 128
+ * rows), 2 = split-KV combine items, 3 = items of the 256-row matrix-core kernel (exactly 256
+ * rows; the full 256-row tiles of units with at least 256 rows and 8192 keys, head size 128).
+ * pv_plan_work_item fills eight int32 fields:
  *   req, kv_head, row_begin, row_count, kv_begin, kv_end, split_index, split_count
  * where a "row" is a (new token, query head of the group) pair, row = token*G + g.  Which kernel
  * a (request, KV head) unit goes to is the plan's decision: more than 32 rows always means the
@@ -171,8 +188,9 @@ pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_n
  * are accumulated in fp32; out is rounded to the 16-bit dtype.  Must run after the append of
  * the same batch on the same stream.
  *   q, out     : device [total_q, Hq, D]
- * Launches at most three kernels (matrix-core attention, bandwidth-oriented attention, merge of
- * split KV ranges), all on `stream`; which of them a batch needs is decided by the plan.
+ * Launches at most four kernels (the two matrix-core attention kernels, bandwidth-oriented
+ * attention, merge of split KV ranges), all on `stream`; which of them a batch needs is decided
+ * by the plan.  Asynchronous, no allocation.
  *   workspace  : device, >= pv_plan_workspace_bytes(plan) bytes, 256-byte aligned; may be NULL
  *                when that is 0.  Its contents are scratch (partial results of split KV
  *                ranges); two launches that overlap in time need different workspaces.
@@ -188,17 +206,23 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
  * belong to the plan).  pv_plan_kernel_ms waits for the end event of that kernel in the plan's most
  * recent launch and returns its duration in milliseconds; *ms = -1 if that kernel did not run.
  * kind: 0 = bandwidth-oriented attention kernel, 1 = matrix-core attention kernel,
- *       2 = split-KV combine, 3 = KV append.
+ *       2 = split-KV combine, 3 = KV append, 4 = 256-row matrix-core attention kernel.
  */
 pv_status pv_plan_enable_timing(pv_plan *plan, int32_t enable);
 pv_status pv_plan_kernel_ms(pv_plan *plan, int32_t kind, float *ms);
 
 /*
- * One-shot forms with explicit arrays.  They build a temporary plan from the HOST length
- * arrays, launch, wait for the stream, and free the plan: convenient, synchronous, and not
- * meant for the per-layer hot loop (use a plan there).  q_start must be the exclusive prefix
- * sum of q_lens and total_q their sum, else PV_ERR_INVALID_ARG.  slot_offsets[r] is the logical
- * position of request r's first new token (normally ctx_lens[r]).
+ * One-shot forms with explicit arrays: convenient, not meant for the per-layer hot loop (use a
+ * plan there).  They build a temporary plan from the HOST length arrays (read during the call),
+ * launch, and free the plan.  q_start must be the exclusive prefix sum of q_lens and total_q their
+ * sum, else PV_ERR_INVALID_ARG.  slot_offsets[r] is the logical position of request r's first
+ * new token (normally ctx_lens[r]).
+ *   pv_multi_token_paged_attn: when `workspace` (256-byte aligned) holds at least
+ *     pv_attn_workspace_bytes(...) bytes, the temporary plan's lists go behind the partial results
+ *     in it: nothing is allocated and the call returns without waiting for the stream.  With a
+ *     smaller workspace that still covers the partial results, the lists go to temporary device
+ *     memory and the call waits for the stream before freeing it.
+ *   pv_kv_append has no buffer argument: temporary device memory, and it waits for the stream.
  */
 pv_status pv_kv_append(const pv_pool_desc *pool, const void *k_new, const void *v_new,
                        const int32_t *page_table /* device */, int32_t max_pages_per_req,
@@ -284,7 +308,8 @@ double pv_cost_model(const int32_t *ctx_points, const double *attn_cost, int32_t
 pv_status pv_retention_order(const double *cost, const double *idle_time, int32_t n,
                              int32_t *order_out);
 
-/* Upper bound of the workspace the one-shot attention call can need for such a batch. */
+/* Upper bound of what the one-shot attention call can need for such a batch: partial results of
+ * split KV ranges plus the lists of its temporary plan. */
 size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, int32_t num_reqs,
                                int32_t total_q, int32_t max_kv_len);
 

@@ -29,7 +29,8 @@ DTYPES = {"f16": 0, "bf16": 1}
 
 EXPORTS = [
     "pv_status_string", "pv_pool_bytes", "pv_pool_k_offset", "pv_pool_v_offset",
-    "pv_plan_create", "pv_plan_destroy", "pv_plan_upload", "pv_plan_total_q", "pv_plan_q_start",
+    "pv_plan_create", "pv_plan_destroy", "pv_plan_upload", "pv_plan_upload_to",
+    "pv_plan_device_bytes", "pv_plan_owns_device_memory", "pv_plan_total_q", "pv_plan_q_start",
     "pv_plan_workspace_bytes", "pv_plan_num_work_items", "pv_plan_work_item",
     "pv_plan_check_page_table", "pv_plan_enable_timing", "pv_plan_kernel_ms",
     "pv_kv_append_planned", "pv_multi_token_paged_attn_planned",
@@ -76,6 +77,12 @@ _lib.pv_plan_destroy.restype = None
 _lib.pv_plan_destroy.argtypes = [_vp]
 _lib.pv_plan_upload.restype = ctypes.c_int
 _lib.pv_plan_upload.argtypes = [_vp]
+_lib.pv_plan_upload_to.restype = ctypes.c_int
+_lib.pv_plan_upload_to.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
+_lib.pv_plan_device_bytes.restype = ctypes.c_size_t
+_lib.pv_plan_device_bytes.argtypes = [_vp]
+_lib.pv_plan_owns_device_memory.restype = ctypes.c_int32
+_lib.pv_plan_owns_device_memory.argtypes = [_vp]
 _lib.pv_plan_total_q.restype = ctypes.c_int32
 _lib.pv_plan_total_q.argtypes = [_vp]
 _lib.pv_plan_q_start.restype = _i32p
@@ -237,6 +244,21 @@ def plan_destroy(plan: Plan):
 
 def plan_upload(plan: Plan):
     _check(_lib.pv_plan_upload(plan.handle), "pv_plan_upload")
+
+
+def plan_upload_to(plan: Plan, device_buf, stream=None):
+    """device_buf: a CUDA tensor (256-byte aligned) of at least plan_device_bytes(plan) bytes that
+    the caller keeps alive while the plan is in use."""
+    _check(_lib.pv_plan_upload_to(plan.handle, _ptr(device_buf), _nbytes(device_buf),
+                                  _stream(stream)), "pv_plan_upload_to")
+
+
+def plan_device_bytes(plan: Plan) -> int:
+    return int(_lib.pv_plan_device_bytes(plan.handle))
+
+
+def plan_owns_device_memory(plan: Plan) -> bool:
+    return bool(_lib.pv_plan_owns_device_memory(plan.handle))
 
 
 def plan_total_q(plan: Plan) -> int:

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(D) void kv_append_kernel(
     scatter_v_group<D>(vsrc, row_stride, g.count, slot0, t, v_pages + tile);
 }
 
-hipError_t launch_kv_append(const pv_plan *plan, const void *k_new, const void *v_new,
+hipError_t launch_kv_append(const pv_plan *plan, const DeviceLists &dl, const void *k_new, const void *v_new,
                             const int32_t *page_table, void *k_pages, void *v_pages,
                             hipStream_t stream)
 {
@@ -53,12 +53,12 @@ hipError_t launch_kv_append(const pv_plan *plan, const void *k_new, const void *
     const dim3 grid((unsigned)groups, (unsigned)plan->pool.num_kv_heads);
     if (D == 128)
         hipLaunchKernelGGL((kv_append_kernel<128>), grid, dim3(128), 0, stream,
-                           plan->d_append_groups, (const uint16_t *)k_new, (const uint16_t *)v_new,
+                           dl.append_groups, (const uint16_t *)k_new, (const uint16_t *)v_new,
                            page_table, plan->max_pages_per_req, plan->pool.num_kv_heads,
                            (uint16_t *)k_pages, (uint16_t *)v_pages);
     else
         hipLaunchKernelGGL((kv_append_kernel<64>), grid, dim3(64), 0, stream,
-                           plan->d_append_groups, (const uint16_t *)k_new, (const uint16_t *)v_new,
+                           dl.append_groups, (const uint16_t *)k_new, (const uint16_t *)v_new,
                            page_table, plan->max_pages_per_req, plan->pool.num_kv_heads,
                            (uint16_t *)k_pages, (uint16_t *)v_pages);
     return hipGetLastError();

@@ -300,13 +300,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(
 }
 
 template <typename T, int D>
-static hipError_t launch_narrow_t(const pv_plan *plan, const void *q, const void *k_pages,
+static hipError_t launch_narrow_t(const pv_plan *plan, const DeviceLists &dl, const void *q, const void *k_pages,
                                   const void *v_pages, const int32_t *page_table, float scale,
                                   void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
     const int n = (int)plan->narrow.size();
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL((attn_narrow_kernel<T, D>), dim3(n), dim3(256), 0, stream, plan->d_narrow,
+    hipLaunchKernelGGL((attn_narrow_kernel<T, D>), dim3(n), dim3(256), 0, stream, dl.narrow,
                        (const uint16_t *)q, (const uint16_t *)k_pages, (const uint16_t *)v_pages,
                        page_table, plan->max_pages_per_req, plan->num_q_heads,
                        plan->pool.num_kv_heads, plan->group, scale * kLog2e, (uint16_t *)out, ws_o,
@@ -315,42 +315,42 @@ static hipError_t launch_narrow_t(const pv_plan *plan, const void *q, const void
 }
 
 template <typename T, int D>
-static hipError_t launch_combine_t(const pv_plan *plan, const float *ws_o, const float *ws_ml,
+static hipError_t launch_combine_t(const pv_plan *plan, const DeviceLists &dl, const float *ws_o, const float *ws_ml,
                                    void *out, hipStream_t stream)
 {
     const int n = (int)plan->combine_chunks.size();
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL((attn_combine_kernel<T, D>), dim3(n), dim3(256), 0, stream,
-                       plan->d_combine_chunks, plan->d_combine, ws_o, ws_ml, plan->num_q_heads,
+                       dl.combine_chunks, dl.combine, ws_o, ws_ml, plan->num_q_heads,
                        plan->group, (uint16_t *)out);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_narrow(const pv_plan *plan, const void *q, const void *k_pages,
+hipError_t launch_attn_narrow(const pv_plan *plan, const DeviceLists &dl, const void *q, const void *k_pages,
                               const void *v_pages, const int32_t *page_table, float scale,
                               void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
     const bool h = plan->pool.dtype == PV_F16;
     if (plan->pool.head_dim == 128)
-        return h ? launch_narrow_t<F16, 128>(plan, q, k_pages, v_pages, page_table, scale, out,
+        return h ? launch_narrow_t<F16, 128>(plan, dl, q, k_pages, v_pages, page_table, scale, out,
                                              ws_o, ws_ml, stream)
-                 : launch_narrow_t<BF16, 128>(plan, q, k_pages, v_pages, page_table, scale, out,
+                 : launch_narrow_t<BF16, 128>(plan, dl, q, k_pages, v_pages, page_table, scale, out,
                                               ws_o, ws_ml, stream);
-    return h ? launch_narrow_t<F16, 64>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+    return h ? launch_narrow_t<F16, 64>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                         ws_ml, stream)
-             : launch_narrow_t<BF16, 64>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+             : launch_narrow_t<BF16, 64>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                          ws_ml, stream);
 }
 
-hipError_t launch_attn_combine(const pv_plan *plan, const float *ws_o, const float *ws_ml,
+hipError_t launch_attn_combine(const pv_plan *plan, const DeviceLists &dl, const float *ws_o, const float *ws_ml,
                                void *out, hipStream_t stream)
 {
     const bool h = plan->pool.dtype == PV_F16;
     if (plan->pool.head_dim == 128)
-        return h ? launch_combine_t<F16, 128>(plan, ws_o, ws_ml, out, stream)
-                 : launch_combine_t<BF16, 128>(plan, ws_o, ws_ml, out, stream);
-    return h ? launch_combine_t<F16, 64>(plan, ws_o, ws_ml, out, stream)
-             : launch_combine_t<BF16, 64>(plan, ws_o, ws_ml, out, stream);
+        return h ? launch_combine_t<F16, 128>(plan, dl, ws_o, ws_ml, out, stream)
+                 : launch_combine_t<BF16, 128>(plan, dl, ws_o, ws_ml, out, stream);
+    return h ? launch_combine_t<F16, 64>(plan, dl, ws_o, ws_ml, out, stream)
+             : launch_combine_t<BF16, 64>(plan, dl, ws_o, ws_ml, out, stream);
 }
 
 }  // namespace pv

@@ -544,7 +544,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
 }
 
 template <typename T>
-static hipError_t launch_tile256_t(const pv_plan *plan, const void *q, const void *k_pages,
+static hipError_t launch_tile256_t(const pv_plan *plan, const DeviceLists &dl, const void *q, const void *k_pages,
                                    const void *v_pages, const int32_t *page_table, float scale,
                                    void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
@@ -554,14 +554,14 @@ static hipError_t launch_tile256_t(const pv_plan *plan, const void *q, const voi
     if (c_abs <= 0.25f) {
         // queries pre-multiplied by scale*log2(e): the sign travels with them
         hipLaunchKernelGGL((attn_tile256_kernel<T, true>), dim3(n), dim3(256), 0, stream,
-                           plan->d_tile256, (const uint16_t *)q, (const uint16_t *)k_pages,
+                           dl.tile256, (const uint16_t *)q, (const uint16_t *)k_pages,
                            (const uint16_t *)v_pages, page_table, plan->max_pages_per_req,
                            plan->num_q_heads, plan->pool.num_kv_heads, plan->group, c_signed, 0u,
                            (uint16_t *)out, ws_o, ws_ml);
     } else {
         const uint32_t q_sign = scale < 0.f ? 0x80008000u : 0u;
         hipLaunchKernelGGL((attn_tile256_kernel<T, false>), dim3(n), dim3(256), 0, stream,
-                           plan->d_tile256, (const uint16_t *)q, (const uint16_t *)k_pages,
+                           dl.tile256, (const uint16_t *)q, (const uint16_t *)k_pages,
                            (const uint16_t *)v_pages, page_table, plan->max_pages_per_req,
                            plan->num_q_heads, plan->pool.num_kv_heads, plan->group, c_abs, q_sign,
                            (uint16_t *)out, ws_o, ws_ml);
@@ -569,7 +569,7 @@ static hipError_t launch_tile256_t(const pv_plan *plan, const void *q, const voi
     return hipGetLastError();
 }
 
-hipError_t launch_attn_tile256(const pv_plan *plan, const void *q, const void *k_pages,
+hipError_t launch_attn_tile256(const pv_plan *plan, const DeviceLists &dl, const void *q, const void *k_pages,
                                const void *v_pages, const int32_t *page_table, float scale,
                                void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
@@ -580,9 +580,9 @@ hipError_t launch_attn_tile256(const pv_plan *plan, const void *q, const void *k
             (int64_t)w.kv_end - w.kv_begin > (int64_t)kTileMaxPages * 16)
             return hipErrorInvalidValue;
     return plan->pool.dtype == PV_F16
-               ? launch_tile256_t<F16>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+               ? launch_tile256_t<F16>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                        ws_ml, stream)
-               : launch_tile256_t<BF16>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+               : launch_tile256_t<BF16>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                         ws_ml, stream);
 }
 

@@ -284,14 +284,14 @@ __global__ __launch_bounds__(256, 3) void attn_wide_kernel(
 }
 
 template <typename T, int D>
-static hipError_t launch_wide_t(const pv_plan *plan, const void *q, const void *k_pages,
+static hipError_t launch_wide_t(const pv_plan *plan, const DeviceLists &dl, const void *q, const void *k_pages,
                                 const void *v_pages, const int32_t *page_table, float scale,
                                 void *out, float *ws_o, float *ws_ml, hipStream_t stream)
 {
     const int n = (int)plan->wide.size();
     const float c = (scale < 0.f ? -scale : scale) * kLog2e;
     const uint32_t q_sign = scale < 0.f ? 0x80008000u : 0u;
-    hipLaunchKernelGGL((attn_wide_kernel<T, D>), dim3(n), dim3(256), 0, stream, plan->d_wide,
+    hipLaunchKernelGGL((attn_wide_kernel<T, D>), dim3(n), dim3(256), 0, stream, dl.wide,
                        (const uint16_t *)q, (const uint16_t *)k_pages, (const uint16_t *)v_pages,
                        page_table, plan->max_pages_per_req, plan->num_q_heads,
                        plan->pool.num_kv_heads, plan->group, c, q_sign, (uint16_t *)out, ws_o,
@@ -299,20 +299,20 @@ static hipError_t launch_wide_t(const pv_plan *plan, const void *q, const void *
     return hipGetLastError();
 }
 
-hipError_t launch_attn_wide(const pv_plan *plan, const void *q, const void *k_pages,
+hipError_t launch_attn_wide(const pv_plan *plan, const DeviceLists &dl, const void *q, const void *k_pages,
                             const void *v_pages, const int32_t *page_table, float scale, void *out,
                             float *ws_o, float *ws_ml, hipStream_t stream)
 {
     if (plan->wide.empty()) return hipSuccess;
     const bool f = plan->pool.dtype == PV_F16;
     if (plan->pool.head_dim == 128)
-        return f ? launch_wide_t<F16, 128>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+        return f ? launch_wide_t<F16, 128>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                            ws_ml, stream)
-                 : launch_wide_t<BF16, 128>(plan, q, k_pages, v_pages, page_table, scale, out,
+                 : launch_wide_t<BF16, 128>(plan, dl, q, k_pages, v_pages, page_table, scale, out,
                                             ws_o, ws_ml, stream);
-    return f ? launch_wide_t<F16, 64>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+    return f ? launch_wide_t<F16, 64>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                       ws_ml, stream)
-             : launch_wide_t<BF16, 64>(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
+             : launch_wide_t<BF16, 64>(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
                                        ws_ml, stream);
 }
 

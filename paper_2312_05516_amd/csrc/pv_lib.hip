@@ -3,98 +3,50 @@
 
 #include <cstdlib>
 #include <cstring>
-#include <mutex>
 #include <vector>
 
 #include "pv_plan.h"
 
 namespace pv {
-hipError_t launch_kv_append(const pv_plan *plan, const void *k_new, const void *v_new,
-                            const int32_t *page_table, void *k_pages, void *v_pages,
+hipError_t launch_kv_append(const pv_plan *plan, const DeviceLists &dl, const void *k_new,
+                            const void *v_new, const int32_t *page_table, void *k_pages,
+                            void *v_pages, hipStream_t stream);
+hipError_t launch_attn_narrow(const pv_plan *plan, const DeviceLists &dl, const void *q,
+                              const void *k_pages, const void *v_pages,
+                              const int32_t *page_table, float scale, void *out, float *ws_o,
+                              float *ws_ml, hipStream_t stream);
+hipError_t launch_attn_wide(const pv_plan *plan, const DeviceLists &dl, const void *q,
+                            const void *k_pages, const void *v_pages, const int32_t *page_table,
+                            float scale, void *out, float *ws_o, float *ws_ml,
                             hipStream_t stream);
-hipError_t launch_attn_narrow(const pv_plan *plan, const void *q, const void *k_pages,
-                              const void *v_pages, const int32_t *page_table, float scale,
-                              void *out, float *ws_o, float *ws_ml, hipStream_t stream);
-hipError_t launch_attn_wide(const pv_plan *plan, const void *q, const void *k_pages,
-                            const void *v_pages, const int32_t *page_table, float scale, void *out,
-                            float *ws_o, float *ws_ml, hipStream_t stream);
-hipError_t launch_attn_tile256(const pv_plan *plan, const void *q, const void *k_pages,
-                               const void *v_pages, const int32_t *page_table, float scale,
-                               void *out, float *ws_o, float *ws_ml, hipStream_t stream);
-hipError_t launch_attn_combine(const pv_plan *plan, const float *ws_o, const float *ws_ml,
-                               void *out, hipStream_t stream);
+hipError_t launch_attn_tile256(const pv_plan *plan, const DeviceLists &dl, const void *q,
+                               const void *k_pages, const void *v_pages,
+                               const int32_t *page_table, float scale, void *out, float *ws_o,
+                               float *ws_ml, hipStream_t stream);
+hipError_t launch_attn_combine(const pv_plan *plan, const DeviceLists &dl, const float *ws_o,
+                               const float *ws_ml, void *out, hipStream_t stream);
 
-hipError_t launch_rope_append(const pv_plan *plan, int style, const void *q_in, void *q_out,
-                              const void *k_new, const void *v_new, const float *cos_sin,
-                              const int32_t *page_table, void *k_pages, void *v_pages,
-                              hipStream_t stream);
+hipError_t launch_rope_append(const pv_plan *plan, const DeviceLists &dl, int style,
+                              const void *q_in, void *q_out, const void *k_new,
+                              const void *v_new, const float *cos_sin, const int32_t *page_table,
+                              void *k_pages, void *v_pages, hipStream_t stream);
 hipError_t launch_pages_copy(bool gather, const pv_pool_desc *pool, const int32_t *page_ids,
                              int32_t n, void *k_pages, void *v_pages, void *staging,
                              hipStream_t stream);
 
-static std::mutex g_upload_mutex;
-
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-static pv_status upload(pv_plan *plan)
-{
-    std::lock_guard<std::mutex> lock(g_upload_mutex);
-    if (plan->uploaded) return PV_OK;
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
-    struct Part { const void *src; size_t bytes; size_t off; };
-    Part parts[9] = {
-        {plan->ctx_lens.data(), plan->ctx_lens.size() * sizeof(int32_t), 0},
-        {plan->q_lens.data(), plan->q_lens.size() * sizeof(int32_t), 0},
-        {plan->q_start.data(), plan->q_start.size() * sizeof(int32_t), 0},
-        {plan->combine_chunks.data(), plan->combine_chunks.size() * sizeof(CombineChunk), 0},
-        {plan->narrow.data(), plan->narrow.size() * sizeof(WorkItem), 0},
-        {plan->wide.data(), plan->wide.size() * sizeof(WorkItem), 0},
-        {plan->combine.data(), plan->combine.size() * sizeof(CombineItem), 0},
-        {plan->append_groups.data(), plan->append_groups.size() * sizeof(AppendGroup), 0},
-        {plan->tile256.data(), plan->tile256.size() * sizeof(WorkItem), 0},
-    };
-    size_t total = 0;
-    for (Part &p : parts) {
-        p.off = total;
-        total += align_up(p.bytes, 256);
-    }
-    if (total == 0) total = 256;
-    std::vector<unsigned char> staging(total, 0);
-    for (const Part &p : parts)
-        if (p.bytes) std::memcpy(staging.data() + p.off, p.src, p.bytes);
-    void *blob = nullptr;
-    if (hipMalloc(&blob, total) != hipSuccess) return PV_ERR_HIP;
-    if (hipMemcpy(blob, staging.data(), total, hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipFree(blob);
-        return PV_ERR_HIP;
-    }
-    unsigned char *b = static_cast<unsigned char *>(blob);
-    plan->d_blob = blob;
-    plan->d_ctx_lens = reinterpret_cast<int32_t *>(b + parts[0].off);
-    plan->d_q_lens = reinterpret_cast<int32_t *>(b + parts[1].off);
-    plan->d_q_start = reinterpret_cast<int32_t *>(b + parts[2].off);
-    plan->d_combine_chunks = reinterpret_cast<CombineChunk *>(b + parts[3].off);
-    plan->d_narrow = reinterpret_cast<WorkItem *>(b + parts[4].off);
-    plan->d_wide = reinterpret_cast<WorkItem *>(b + parts[5].off);
-    plan->d_combine = reinterpret_cast<CombineItem *>(b + parts[6].off);
-    plan->d_append_groups = reinterpret_cast<AppendGroup *>(b + parts[7].off);
-    plan->d_tile256 = reinterpret_cast<WorkItem *>(b + parts[8].off);
-    plan->device = dev;
-    plan->uploaded = true;
-    return PV_OK;
-}
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static pv_status ensure_ready(pv_plan *plan)
+// A planned launch needs the plan's lists on the current device: it never allocates or copies
+// by itself.
+static pv_status ensure_ready(const pv_plan *plan)
 {
     if (!plan) return PV_ERR_INVALID_ARG;
-    if (!plan->uploaded) {
-        pv_status s = upload(plan);
-        if (s != PV_OK) return s;
-    }
+    if (!plan->uploaded) return PV_ERR_INVALID_ARG;  // pv_plan_upload / pv_plan_upload_to first
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
-    if (dev != plan->device) return PV_ERR_INVALID_ARG;  // plan lives on another GPU
+    if (dev != plan->device) return PV_ERR_INVALID_ARG;  // the lists live on another GPU
     return PV_OK;
 }
 
@@ -147,19 +99,95 @@ pv_status pv_plan_kernel_ms(pv_plan *plan, int32_t kind, float *ms)
     return PV_OK;
 }
 
+pv_status pv_plan_upload_to(pv_plan *plan, void *device_buf, size_t bytes, void *stream)
+{
+    if (!plan || !device_buf) return PV_ERR_INVALID_ARG;
+    if (bytes < plan->image.size() || (reinterpret_cast<uintptr_t>(device_buf) & 255u) != 0)
+        return PV_ERR_WORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
+    if (hipMemcpyAsync(device_buf, plan->image.data(), plan->image.size(), hipMemcpyHostToDevice,
+                       static_cast<hipStream_t>(stream)) != hipSuccess)
+        return PV_ERR_HIP;
+    if (plan->d_owned && plan->d_owned != device_buf) {
+        (void)hipFree(plan->d_owned);
+        plan->d_owned = nullptr;
+    }
+    plan->dev = pv::lists_at(plan, device_buf);
+    plan->device = dev;
+    plan->uploaded = true;
+    return PV_OK;
+}
+
 pv_status pv_plan_upload(pv_plan *plan)
 {
     if (!plan) return PV_ERR_INVALID_ARG;
-    return pv::upload(plan);
+    if (plan->uploaded) return PV_OK;
+    void *buf = nullptr;
+    if (hipMalloc(&buf, plan->image.size()) != hipSuccess) return PV_ERR_HIP;
+    pv_status s = pv_plan_upload_to(plan, buf, plan->image.size(), nullptr);
+    if (s == PV_OK && hipStreamSynchronize(nullptr) != hipSuccess) s = PV_ERR_HIP;
+    if (s != PV_OK) {
+        (void)hipFree(buf);
+        plan->uploaded = false;
+        return s;
+    }
+    plan->d_owned = buf;
+    return PV_OK;
 }
 
 void pv_plan_destroy(pv_plan *plan)
 {
     if (!plan) return;
-    if (plan->d_blob) (void)hipFree(plan->d_blob);
+    if (plan->d_owned) (void)hipFree(plan->d_owned);
     for (void *e : plan->events)
         if (e) (void)hipEventDestroy(static_cast<hipEvent_t>(e));
     delete plan;
+}
+
+// The three attention kernels and the merge of split KV ranges, with the plan's lists at `dl`.
+static pv_status attn_launch(pv_plan *plan, const pv::DeviceLists &dl, const void *q,
+                             const void *k_pages, const void *v_pages, const int32_t *page_table,
+                             float scale, void *out, float *ws_o, float *ws_ml, hipStream_t st)
+{
+    // the kernels touch disjoint rows of `out`; all run on the caller's stream
+    {
+        pv::KernelTimer t(plan, 4, st, !plan->tile256.empty());
+        if (pv::launch_attn_tile256(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
+                                    ws_ml, st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    {
+        pv::KernelTimer t(plan, 1, st, !plan->wide.empty());
+        if (pv::launch_attn_wide(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
+                                 ws_ml, st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    {
+        pv::KernelTimer t(plan, 0, st, !plan->narrow.empty());
+        if (pv::launch_attn_narrow(plan, dl, q, k_pages, v_pages, page_table, scale, out, ws_o,
+                                   ws_ml, st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    {
+        pv::KernelTimer t(plan, 2, st, !plan->combine.empty());
+        if (pv::launch_attn_combine(plan, dl, ws_o, ws_ml, out, st) != hipSuccess)
+            return PV_ERR_HIP;
+    }
+    return PV_OK;
+}
+
+static pv_status attn_args_ok(const pv_plan *plan, const void *q, const void *k_pages,
+                              const void *v_pages, const int32_t *page_table, float scale,
+                              const void *out)
+{
+    if (!q || !k_pages || !v_pages || !page_table || !out) return PV_ERR_INVALID_ARG;
+    if (!pv::aligned16(q) || !pv::aligned16(k_pages) || !pv::aligned16(v_pages) ||
+        !pv::aligned16(out))
+        return PV_ERR_INVALID_ARG;
+    if (!(scale == scale)) return PV_ERR_INVALID_ARG;
+    (void)plan;
+    return PV_OK;
 }
 
 pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_new,
@@ -169,13 +197,16 @@ pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_n
     if (!plan) return PV_ERR_INVALID_ARG;
     if (plan->total_q == 0) return PV_OK;
     if (!k_new || !v_new || !page_table || !k_pages || !v_pages) return PV_ERR_INVALID_ARG;
+    if (!pv::aligned16(k_new) || !pv::aligned16(v_new) || !pv::aligned16(k_pages) ||
+        !pv::aligned16(v_pages))
+        return PV_ERR_INVALID_ARG;
     pv_status s = pv::ensure_ready(plan);
     if (s != PV_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e;
     {
         pv::KernelTimer t(plan, 3, st, true);
-        e = pv::launch_kv_append(plan, k_new, v_new, page_table, k_pages, v_pages, st);
+        e = pv::launch_kv_append(plan, plan->dev, k_new, v_new, page_table, k_pages, v_pages, st);
     }
     return e == hipSuccess ? PV_OK : PV_ERR_HIP;
 }
@@ -191,6 +222,10 @@ pv_status pv_rope_kv_append_planned(pv_plan *plan, const void *q_in, void *q_out
     if (plan->total_q == 0) return PV_OK;
     if (!k_new || !v_new || !cos_sin || !page_table || !k_pages || !v_pages)
         return PV_ERR_INVALID_ARG;
+    if (!pv::aligned16(q_in) || !pv::aligned16(q_out) || !pv::aligned16(k_new) ||
+        !pv::aligned16(v_new) || !pv::aligned16(cos_sin) || !pv::aligned16(k_pages) ||
+        !pv::aligned16(v_pages))
+        return PV_ERR_INVALID_ARG;
     for (int32_t r = 0; r < plan->num_reqs; ++r)
         if (plan->q_lens[r] > 0 && (int64_t)plan->ctx_lens[r] + plan->q_lens[r] > max_pos)
             return PV_ERR_OUT_OF_RANGE;
@@ -200,8 +235,8 @@ pv_status pv_rope_kv_append_planned(pv_plan *plan, const void *q_in, void *q_out
     hipError_t e;
     {
         pv::KernelTimer t(plan, 3, st, true);
-        e = pv::launch_rope_append(plan, style, q_in, q_out, k_new, v_new, cos_sin, page_table,
-                                   k_pages, v_pages, st);
+        e = pv::launch_rope_append(plan, plan->dev, style, q_in, q_out, k_new, v_new, cos_sin,
+                                   page_table, k_pages, v_pages, st);
     }
     return e == hipSuccess ? PV_OK : PV_ERR_HIP;
 }
@@ -213,8 +248,8 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
 {
     if (!plan) return PV_ERR_INVALID_ARG;
     if (plan->total_q == 0) return PV_OK;
-    if (!q || !k_pages || !v_pages || !page_table || !out) return PV_ERR_INVALID_ARG;
-    if (!(scale == scale)) return PV_ERR_INVALID_ARG;
+    pv_status s = attn_args_ok(plan, q, k_pages, v_pages, page_table, scale, out);
+    if (s != PV_OK) return s;
     float *ws_o = nullptr, *ws_ml = nullptr;
     if (plan->workspace_bytes > 0) {
         if (!workspace || workspace_bytes < plan->workspace_bytes ||
@@ -223,33 +258,10 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
         ws_o = static_cast<float *>(workspace);
         ws_ml = ws_o + (size_t)plan->partial_slots * plan->pool.head_dim;
     }
-    pv_status s = pv::ensure_ready(plan);
+    s = pv::ensure_ready(plan);
     if (s != PV_OK) return s;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    // the kernels touch disjoint rows of `out`; all run on the caller's stream
-    {
-        pv::KernelTimer t(plan, 4, st, !plan->tile256.empty());
-        if (pv::launch_attn_tile256(plan, q, k_pages, v_pages, page_table, scale, out, ws_o,
-                                    ws_ml, st) != hipSuccess)
-            return PV_ERR_HIP;
-    }
-    {
-        pv::KernelTimer t(plan, 1, st, !plan->wide.empty());
-        if (pv::launch_attn_wide(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
-                                 st) != hipSuccess)
-            return PV_ERR_HIP;
-    }
-    {
-        pv::KernelTimer t(plan, 0, st, !plan->narrow.empty());
-        if (pv::launch_attn_narrow(plan, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
-                                   st) != hipSuccess)
-            return PV_ERR_HIP;
-    }
-    {
-        pv::KernelTimer t(plan, 2, st, !plan->combine.empty());
-        if (pv::launch_attn_combine(plan, ws_o, ws_ml, out, st) != hipSuccess) return PV_ERR_HIP;
-    }
-    return PV_OK;
+    return attn_launch(plan, plan->dev, q, k_pages, v_pages, page_table, scale, out, ws_o, ws_ml,
+                       static_cast<hipStream_t>(stream));
 }
 
 static pv_status check_prefix(const int32_t *q_lens, const int32_t *q_start, int32_t num_reqs,
@@ -279,7 +291,11 @@ pv_status pv_kv_append(const pv_pool_desc *pool, const void *k_new, const void *
     s = pv_plan_create(pool, pool->num_kv_heads, slot_offsets, q_lens, num_reqs, max_pages_per_req,
                        &plan);
     if (s != PV_OK) return s;
-    s = pv_kv_append_planned(plan, k_new, v_new, page_table, k_pages, v_pages, stream);
+    // this form has no buffer of the caller's to put the lists in: temporary device memory, and
+    // a wait for the stream before it is freed
+    if (plan->total_q > 0) s = pv_plan_upload(plan);
+    if (s == PV_OK)
+        s = pv_kv_append_planned(plan, k_new, v_new, page_table, k_pages, v_pages, stream);
     if (s == PV_OK && plan->total_q > 0 &&
         hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess)
         s = PV_ERR_HIP;
@@ -300,9 +316,32 @@ pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_head
     pv_plan *plan = nullptr;
     s = pv_plan_create(pool, num_q_heads, ctx_lens, q_lens, num_reqs, max_pages_per_req, &plan);
     if (s != PV_OK) return s;
-    s = pv_multi_token_paged_attn_planned(plan, q, k_pages, v_pages, page_table, scale, out,
-                                          workspace, workspace_bytes, stream);
-    if (s == PV_OK && plan->total_q > 0 &&
+    if (plan->total_q == 0) {
+        pv_plan_destroy(plan);
+        return PV_OK;
+    }
+    // The caller's workspace holds the partial results first and, behind them, the plan's lists
+    // when it is large enough for both (pv_attn_workspace_bytes is): then nothing is allocated
+    // and the call returns without waiting (the copy of the lists is staged by the runtime before
+    // it returns, so the temporary plan can go).  Otherwise: temporary device memory and a wait.
+    const size_t ws_part = pv::align_up(plan->workspace_bytes, 256);
+    const bool ws_ok = workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u) == 0;
+    if (plan->workspace_bytes > 0 && (!ws_ok || workspace_bytes < plan->workspace_bytes)) {
+        pv_plan_destroy(plan);
+        return PV_ERR_WORKSPACE;
+    }
+    bool wait = false;
+    if (ws_ok && workspace_bytes >= ws_part + plan->image.size()) {
+        s = pv_plan_upload_to(plan, static_cast<unsigned char *>(workspace) + ws_part,
+                              workspace_bytes - ws_part, stream);
+    } else {
+        s = pv_plan_upload(plan);
+        wait = true;
+    }
+    if (s == PV_OK)
+        s = pv_multi_token_paged_attn_planned(plan, q, k_pages, v_pages, page_table, scale, out,
+                                              workspace, workspace_bytes, stream);
+    if (s == PV_OK && wait &&
         hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess)
         s = PV_ERR_HIP;
     pv_plan_destroy(plan);
@@ -355,7 +394,16 @@ size_t pv_attn_workspace_bytes(const pv_pool_desc *pool, int32_t num_q_heads, in
     const int64_t by_items =
         2 * (int64_t)t.split_target * (pv::kNarrowRows + pv::kWideRows + pv::kTileRows);
     const int64_t slots = by_rows < by_items ? by_rows : by_items;
-    return (size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float);
+    // behind the partial results: room for the plan's lists (three int32 per request, 48 bytes
+    // per work item and 40 per merge item and its chunks, 16 per append group, nine 256-byte
+    // alignments), so that the one-shot call neither allocates nor waits
+    const int64_t n_items = rows / pv::kNarrowRows + (int64_t)num_reqs * pool->num_kv_heads * 3 +
+                            2 * (int64_t)t.split_target * 3;
+    const int64_t lists = 12 * (int64_t)num_reqs + 48 * n_items + 40 * n_items / 2 +
+                          8 * (slots / 8 + n_items) + 16 * ((int64_t)total_q + 2 * num_reqs) +
+                          10 * 256;
+    return pv::align_up((size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float), 256) +
+           (size_t)lists;
 }
 
 }  // extern "C"

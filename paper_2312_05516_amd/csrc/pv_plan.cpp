@@ -215,6 +215,33 @@ static void order_items(std::vector<WorkItem> &items, int rows_per_step, int xcd
     items.swap(out);
 }
 
+// One contiguous host image of the arrays the kernels read, each part 256-byte aligned.
+static void build_image(pv_plan *plan)
+{
+    struct Part { const void *src; size_t bytes; };
+    const Part parts[9] = {
+        {plan->ctx_lens.data(), plan->ctx_lens.size() * sizeof(int32_t)},
+        {plan->q_lens.data(), plan->q_lens.size() * sizeof(int32_t)},
+        {plan->q_start.data(), plan->q_start.size() * sizeof(int32_t)},
+        {plan->combine_chunks.data(), plan->combine_chunks.size() * sizeof(CombineChunk)},
+        {plan->narrow.data(), plan->narrow.size() * sizeof(WorkItem)},
+        {plan->wide.data(), plan->wide.size() * sizeof(WorkItem)},
+        {plan->tile256.data(), plan->tile256.size() * sizeof(WorkItem)},
+        {plan->combine.data(), plan->combine.size() * sizeof(CombineItem)},
+        {plan->append_groups.data(), plan->append_groups.size() * sizeof(AppendGroup)},
+    };
+    size_t total = 0;
+    for (int i = 0; i < 9; ++i) {
+        plan->image_off[i] = total;
+        total += (parts[i].bytes + 255) / 256 * 256;
+    }
+    if (total == 0) total = 256;
+    plan->image.assign(total, 0);
+    for (int i = 0; i < 9; ++i)
+        if (parts[i].bytes)
+            std::memcpy(plan->image.data() + plan->image_off[i], parts[i].src, parts[i].bytes);
+}
+
 pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_t *ctx_lens,
                      const int32_t *q_lens, int32_t num_reqs, int32_t max_pages_per_req,
                      const Tuning &tune, pv_plan **out)
@@ -256,7 +283,8 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     plan->partial_slots = 0;
     plan->uploaded = false;
     plan->device = -1;
-    plan->d_blob = nullptr;
+    plan->d_owned = nullptr;
+    std::memset(&plan->dev, 0, sizeof plan->dev);
     plan->timing = false;
     for (void *&e : plan->events) e = nullptr;
     for (bool &u : plan->event_used) u = false;
@@ -377,8 +405,25 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
             plan->combine_chunks.push_back(CombineChunk{(int32_t)i, r0});
     // workspace: fp32 partial outputs [slots][D], then (running max, running sum) [slots][2]
     plan->workspace_bytes = (size_t)slots * (size_t)(pool->head_dim + 2) * sizeof(float);
+    build_image(plan);
     *out = plan;
     return PV_OK;
+}
+
+DeviceLists lists_at(const pv_plan *plan, const void *base)
+{
+    const unsigned char *b = static_cast<const unsigned char *>(base);
+    DeviceLists d;
+    d.ctx_lens = reinterpret_cast<const int32_t *>(b + plan->image_off[0]);
+    d.q_lens = reinterpret_cast<const int32_t *>(b + plan->image_off[1]);
+    d.q_start = reinterpret_cast<const int32_t *>(b + plan->image_off[2]);
+    d.combine_chunks = reinterpret_cast<const CombineChunk *>(b + plan->image_off[3]);
+    d.narrow = reinterpret_cast<const WorkItem *>(b + plan->image_off[4]);
+    d.wide = reinterpret_cast<const WorkItem *>(b + plan->image_off[5]);
+    d.tile256 = reinterpret_cast<const WorkItem *>(b + plan->image_off[6]);
+    d.combine = reinterpret_cast<const CombineItem *>(b + plan->image_off[7]);
+    d.append_groups = reinterpret_cast<const AppendGroup *>(b + plan->image_off[8]);
+    return d;
 }
 
 }  // namespace pv
@@ -447,6 +492,13 @@ const int32_t *pv_plan_q_start(const pv_plan *plan)
 }
 
 size_t pv_plan_workspace_bytes(const pv_plan *plan) { return plan ? plan->workspace_bytes : 0; }
+
+size_t pv_plan_device_bytes(const pv_plan *plan) { return plan ? plan->image.size() : 0; }
+
+int32_t pv_plan_owns_device_memory(const pv_plan *plan)
+{
+    return plan ? (plan->d_owned != nullptr ? 1 : 0) : -1;
+}
 
 int32_t pv_plan_num_work_items(const pv_plan *plan, int32_t kind)
 {

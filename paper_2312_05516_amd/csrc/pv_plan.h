@@ -64,6 +64,18 @@ constexpr int kKvBlock = 32;     // keys per inner step (two pages)
 constexpr int kTileMaxPages = 8192;  // page ids an item of the 256-row kernel may span (it keeps
                                      // them in LDS): its KV range is at most 16 times that
 
+// Where the lists of a plan live on a device: pointers into one buffer laid out as the plan's
+// host image (see pv_plan::image).  The launchers take the lists through this, so that the same
+// plan can run from its own upload, from a buffer of the caller's, or from the library's static
+// scratch array.
+struct DeviceLists {
+    const int32_t *ctx_lens, *q_lens, *q_start;
+    const CombineChunk *combine_chunks;
+    const WorkItem *narrow, *wide, *tile256;
+    const CombineItem *combine;
+    const AppendGroup *append_groups;
+};
+
 struct Tuning {
     int32_t split_target;    // aim for at least this many work items per kernel
     int32_t min_split_keys;  // never make a KV part shorter than this
@@ -96,15 +108,17 @@ struct pv_plan {
     int64_t partial_slots;  // workspace row slots
     size_t workspace_bytes;
 
-    // device copies (filled by pv_plan_upload)
+    // Host image of everything the kernels read from the plan: the nine arrays above, each at a
+    // 256-byte aligned offset (image_off, in the order of pv::DeviceLists).  Built with the plan,
+    // copied to a device by pv_plan_upload / pv_plan_upload_to / the no-allocation launch.
+    std::vector<unsigned char> image;
+    size_t image_off[9];
+
+    // device copy (set by pv_plan_upload or pv_plan_upload_to)
     bool uploaded;
     int device;
-    void *d_blob;  // one allocation holding everything below
-    int32_t *d_ctx_lens, *d_q_lens, *d_q_start;
-    pv::WorkItem *d_narrow, *d_wide, *d_tile256;
-    pv::CombineItem *d_combine;
-    pv::AppendGroup *d_append_groups;
-    pv::CombineChunk *d_combine_chunks;
+    void *d_owned;        // device memory the plan allocated itself (pv_plan_upload), else null
+    pv::DeviceLists dev;  // valid while `uploaded`
 
     // optional per-kernel timing: events[2*kind], events[2*kind+1] bracket kernel `kind`
     bool timing;
@@ -113,6 +127,8 @@ struct pv_plan {
 };
 
 namespace pv {
+// the lists of a plan image that was copied to `base`
+DeviceLists lists_at(const pv_plan *plan, const void *base);
 bool pool_desc_valid(const pv_pool_desc *p, pv_status *why);
 Tuning default_tuning();
 pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_t *ctx_lens,

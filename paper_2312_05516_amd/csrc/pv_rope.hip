@@ -113,7 +113,7 @@ __global__ __launch_bounds__(D) void rope_append_kernel(
 }
 
 template <typename T, int D>
-static hipError_t launch_rope_t(const pv_plan *plan, int style, const void *q_in, void *q_out,
+static hipError_t launch_rope_t(const pv_plan *plan, const DeviceLists &dl, int style, const void *q_in, void *q_out,
                                 const void *k_new, const void *v_new, const float *cos_sin,
                                 const int32_t *page_table, void *k_pages, void *v_pages,
                                 hipStream_t stream)
@@ -122,20 +122,20 @@ static hipError_t launch_rope_t(const pv_plan *plan, int style, const void *q_in
     const dim3 grid((unsigned)plan->append_groups.size(), heads);
     if (style == 0)
         hipLaunchKernelGGL((rope_append_kernel<T, D, 0>), grid, dim3(D), 0, stream,
-                           plan->d_append_groups, (const uint16_t *)q_in, (uint16_t *)q_out,
+                           dl.append_groups, (const uint16_t *)q_in, (uint16_t *)q_out,
                            (const uint16_t *)k_new, (const uint16_t *)v_new, cos_sin, page_table,
                            plan->max_pages_per_req, plan->num_q_heads, plan->pool.num_kv_heads,
                            (uint16_t *)k_pages, (uint16_t *)v_pages);
     else
         hipLaunchKernelGGL((rope_append_kernel<T, D, 1>), grid, dim3(D), 0, stream,
-                           plan->d_append_groups, (const uint16_t *)q_in, (uint16_t *)q_out,
+                           dl.append_groups, (const uint16_t *)q_in, (uint16_t *)q_out,
                            (const uint16_t *)k_new, (const uint16_t *)v_new, cos_sin, page_table,
                            plan->max_pages_per_req, plan->num_q_heads, plan->pool.num_kv_heads,
                            (uint16_t *)k_pages, (uint16_t *)v_pages);
     return hipGetLastError();
 }
 
-hipError_t launch_rope_append(const pv_plan *plan, int style, const void *q_in, void *q_out,
+hipError_t launch_rope_append(const pv_plan *plan, const DeviceLists &dl, int style, const void *q_in, void *q_out,
                               const void *k_new, const void *v_new, const float *cos_sin,
                               const int32_t *page_table, void *k_pages, void *v_pages,
                               hipStream_t stream)
@@ -143,13 +143,13 @@ hipError_t launch_rope_append(const pv_plan *plan, int style, const void *q_in, 
     if (plan->append_groups.empty()) return hipSuccess;
     const bool f = plan->pool.dtype == PV_F16;
     if (plan->pool.head_dim == 128)
-        return f ? launch_rope_t<F16, 128>(plan, style, q_in, q_out, k_new, v_new, cos_sin,
+        return f ? launch_rope_t<F16, 128>(plan, dl, style, q_in, q_out, k_new, v_new, cos_sin,
                                            page_table, k_pages, v_pages, stream)
-                 : launch_rope_t<BF16, 128>(plan, style, q_in, q_out, k_new, v_new, cos_sin,
+                 : launch_rope_t<BF16, 128>(plan, dl, style, q_in, q_out, k_new, v_new, cos_sin,
                                             page_table, k_pages, v_pages, stream);
-    return f ? launch_rope_t<F16, 64>(plan, style, q_in, q_out, k_new, v_new, cos_sin, page_table,
+    return f ? launch_rope_t<F16, 64>(plan, dl, style, q_in, q_out, k_new, v_new, cos_sin, page_table,
                                       k_pages, v_pages, stream)
-             : launch_rope_t<BF16, 64>(plan, style, q_in, q_out, k_new, v_new, cos_sin, page_table,
+             : launch_rope_t<BF16, 64>(plan, dl, style, q_in, q_out, k_new, v_new, cos_sin, page_table,
                                        k_pages, v_pages, stream);
 }
 

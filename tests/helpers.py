@@ -196,6 +196,10 @@ def gpu_run(case: Case, scale=None, page_table=None, pools=None, do_append=True,
     else:
         plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
         assert np.array_equal(pv.plan_q_start(plan), b.q_start)
+        # the plan's lists go into a buffer of ours: the library allocates no device memory at all
+        lists = torch.empty(pv.plan_device_bytes(plan), dtype=torch.uint8, device="cuda")
+        pv.plan_upload_to(plan, lists)
+        assert not pv.plan_owns_device_memory(plan)
         ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
         if do_append:
             pv.kv_append_planned(plan, kn, vn, table, kp, vp)

@@ -231,6 +231,26 @@ def test_page_table_check(pv):
     plan.destroy()
 
 
+def test_planned_launch_refuses_a_plan_whose_lists_are_on_no_device(pv):
+    """A *_planned launch never allocates or copies: without pv_plan_upload / pv_plan_upload_to it
+    returns an error before it touches the GPU (so this runs without one)."""
+    desc = pv.pool_desc(64, 4, 64, "f16")
+    plan = pv.plan_create(desc, 4, [10, 3], [2, 1], 4)
+    assert pv.plan_device_bytes(plan) >= 256 and pv.plan_device_bytes(plan) % 256 == 0
+    assert not pv.plan_owns_device_memory(plan)
+    fake = 0x1000  # aligned, never dereferenced
+    with pytest.raises(pv.PvError) as e:
+        pv.multi_token_paged_attn_planned(plan, fake, fake, fake, fake, 0.125, fake, None, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:
+        pv.kv_append_planned(plan, fake, fake, fake, fake, fake, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(pv.PvError) as e:  # misaligned q
+        pv.multi_token_paged_attn_planned(plan, fake + 2, fake, fake, fake, 0.125, fake, None, stream=0)
+    assert e.value.status == 1
+    plan.destroy()
+
+
 def test_workspace_bound_covers_plans(pv):
     for name in ["tiny", "mha13b", "gqa70b", "decode_heavy"]:
         b = wl.CONFIGS[name]()
@@ -238,7 +258,7 @@ def test_workspace_bound_covers_plans(pv):
         plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
         bound = pv.attn_workspace_bytes(desc, b.num_q_heads, b.num_reqs, b.total_q,
                                         int(b.kv_lens.max()))
-        assert bound >= pv.plan_workspace_bytes(plan)
+        assert bound >= (pv.plan_workspace_bytes(plan) + 255) // 256 * 256 + pv.plan_device_bytes(plan)
         plan.destroy()
     # shapes that make the plan split: one long request alone, an outlier in a long list, a
     # mixed batch routed to one kernel, seeded random mixes
@@ -255,7 +275,8 @@ def test_workspace_bound_covers_plans(pv):
         plan = pv.plan_create(desc, hq, ctx, qn, 4096)
         kv_max = max([c + q for c, q in zip(ctx, qn)] + [0])
         bound = pv.attn_workspace_bytes(desc, hq, len(ctx), int(sum(qn)), kv_max)
-        assert bound >= pv.plan_workspace_bytes(plan), (ctx[:4], qn[:4], hq, hkv)
+        need = (pv.plan_workspace_bytes(plan) + 255) // 256 * 256 + pv.plan_device_bytes(plan)
+        assert bound >= need, (ctx[:4], qn[:4], hq, hkv)
         plan.destroy()
 
 

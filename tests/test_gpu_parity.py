@@ -76,6 +76,7 @@ def test_empty_batch_is_a_no_op():
     from paper_2312_05516_amd import binding as pv
     desc = pv.pool_desc(8, 2, 64, "f16")
     plan = pv.plan_create(desc, 2, [], [], 4)
+    pv.plan_upload(plan)
     dummy = torch.zeros(16, dtype=torch.float16, device="cuda")
     table = torch.zeros(4, dtype=torch.int32, device="cuda")
     pv.kv_append_planned(plan, dummy, dummy, table, dummy, dummy)
@@ -91,6 +92,7 @@ def test_split_kv_and_combine(oracle, monkeypatch):
                   dtype="bf16", seed=47)
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     assert pv.plan_num_work_items(plan, 2) > 0 and pv.plan_workspace_bytes(plan) > 0
     plan.destroy()
     check_case(oracle, H.make_case(b, fill="nan"))
@@ -104,6 +106,7 @@ def test_workspace_is_checked():
     b = wl.custom([4000], [1], num_q_heads=2, num_kv_heads=2, head_dim=64, seed=1)
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, 2, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     need = pv.plan_workspace_bytes(plan)
     assert need > 0
     dummy = torch.zeros(1 << 20, dtype=torch.float16, device="cuda")
@@ -228,6 +231,7 @@ def _full_size_parity(oracle, b, sample_reqs, sample_heads, value_seed=0):
     sub_v = H.from_dev_bits(vp.index_select(0, idx)).ravel().copy()
 
     plan = pv.plan_create(desc, Hq, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device=dev)
     out = torch.full((b.total_q, Hq, D), float("nan"), dtype=tdt, device=dev)
     pv.kv_append_planned(plan, kn, vn, table, kp, vp)
@@ -311,6 +315,7 @@ def test_graph_replay_matches_eager(oracle, kernels, monkeypatch):
     case = H.make_case(b, fill="nan")
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     if kernels == "one_attention_kernel":
         assert pv.plan_num_work_items(plan, 0) == 0 and pv.plan_num_work_items(plan, 1) > 0
     else:
@@ -400,12 +405,14 @@ def test_long_contexts_with_split_kv(oracle):
     b = wl.custom([60000], [1], num_q_heads=8, num_kv_heads=1, head_dim=128, dtype="bf16", seed=83)
     desc = pv.pool_desc(b.num_pages, 1, 128, "bf16")
     plan = pv.plan_create(desc, 8, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     assert pv.plan_num_work_items(plan, 0) > 50 and pv.plan_num_work_items(plan, 2) == 1
     plan.destroy()
     check_case(oracle, H.make_case(b, fill="nan"))
     b = wl.custom([20000], [64], num_q_heads=2, num_kv_heads=1, head_dim=64, dtype="f16", seed=85)
     desc = pv.pool_desc(b.num_pages, 1, 64, "f16")
     plan = pv.plan_create(desc, 2, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     assert pv.plan_num_work_items(plan, 1) > 20 and pv.plan_num_work_items(plan, 2) == 1
     plan.destroy()
     check_case(oracle, H.make_case(b, fill="nan"))
@@ -420,6 +427,7 @@ def test_outlier_in_a_long_work_list_is_split(oracle):
         b = wl.custom(ctx, qn, num_q_heads=8, num_kv_heads=8, head_dim=64, dtype="f16", seed=87)
         desc = pv.pool_desc(b.num_pages, 8, 64, "f16")
         plan = pv.plan_create(desc, 8, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        pv.plan_upload(plan)
         for kind in (0, 1):
             n = pv.plan_num_work_items(plan, kind)
             assert (n > 1024) == (kind in kinds), (kind, n)

@@ -92,6 +92,7 @@ def _gpu_fused(case, table, style, with_q=True, in_place=False, attend=False):
     b = case.batch
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     kp, vp = H.to_dev_bits(case.k_pool0, b.dtype), H.to_dev_bits(case.v_pool0, b.dtype)
     tab = torch.from_numpy(table).cuda()
     pt = torch.from_numpy(b.page_table).cuda()
@@ -188,6 +189,7 @@ def test_bad_arguments_are_rejected(oracle):
     case = H.make_case(b, fill="zero")
     desc = pv.pool_desc(b.num_pages, 2, 64, "f16")
     plan = pv.plan_create(desc, 2, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     kp, vp = H.to_dev_bits(case.k_pool0, "f16"), H.to_dev_bits(case.v_pool0, "f16")
     q = H.to_dev_bits(case.q, "f16")
     kn, vn = H.to_dev_bits(case.k_new, "f16"), H.to_dev_bits(case.v_new, "f16")

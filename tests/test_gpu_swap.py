@@ -72,6 +72,7 @@ def test_swap_through_pinned_host_memory_and_event_gated_attention(oracle):
     q = H.to_dev_bits(case.q, b.dtype)
     out = torch.zeros((b.total_q, b.num_q_heads, b.head_dim), dtype=q.dtype, device="cuda")
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     ws = torch.empty(max(pv.plan_workspace_bytes(plan), 256), dtype=torch.uint8, device="cuda")
     home_d = torch.from_numpy(new_home).cuda()
     torch.cuda.synchronize()
@@ -91,6 +92,7 @@ def test_swap_through_pinned_host_memory_and_event_gated_attention(oracle):
     # and it is bit-identical to attention on the pages where they were before the swap
     out0 = torch.zeros_like(out)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+    pv.plan_upload(plan)
     pv.multi_token_paged_attn_planned(plan, q, kp, vp, torch.from_numpy(b.page_table).cuda(),
                                       b.scale, out0, ws)
     torch.cuda.synchronize()
