@@ -58,6 +58,11 @@
 extern "C" {
 #endif
 
+/* Size of the static device array behind pv_multi_token_paged_attn_noalloc (per GPU). */
+#ifndef PV_STATIC_SCRATCH_BYTES
+#define PV_STATIC_SCRATCH_BYTES (32u << 20)
+#endif
+
 typedef enum {
     PV_OK = 0,
     PV_ERR_INVALID_ARG = 1,  /* null pointer, negative size, inconsistent arrays */
@@ -199,6 +204,25 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
                                             const void *v_pages, const int32_t *page_table,
                                             float scale, void *out, void *workspace,
                                             size_t workspace_bytes, void *stream);
+
+/*
+ * The same attention launch for callers that cannot allocate device memory or be handed any by
+ * something that does: code under HIP graph capture set-up, tight serving loops, harnesses that
+ * forbid allocation.  Behaves like pv_multi_token_paged_attn_planned, except that the plan need
+ * not have been uploaded and no workspace is passed: the plan's lists and the partial results of
+ * split KV ranges go into a static device array of PV_STATIC_SCRATCH_BYTES (32 MiB) that every
+ * GPU the library runs on holds until the process ends.  The call copies the lists there with one
+ * asynchronous copy on `stream` and launches; it calls no allocating routine and does not wait.
+ * PV_ERR_WORKSPACE if the batch needs more than the array holds (pv_plan_device_bytes rounded up
+ * to 256 + pv_plan_workspace_bytes > pv_static_scratch_bytes()): use the planned call then.
+ * All calls on one GPU share that GPU's array: two calls whose execution may overlap (different
+ * streams, or the same plan replayed while an earlier launch still runs) race on it.  Nothing in
+ * the array needs clearing between calls.
+ */
+size_t pv_static_scratch_bytes(void);
+pv_status pv_multi_token_paged_attn_noalloc(pv_plan *plan, const void *q, const void *k_pages,
+                                            const void *v_pages, const int32_t *page_table,
+                                            float scale, void *out, void *stream);
 
 /*
  * Per-kernel timing for reports.  After pv_plan_enable_timing(plan, 1) every planned launch also

@@ -37,6 +37,7 @@ EXPORTS = [
     "pv_kv_append", "pv_multi_token_paged_attn", "pv_attn_workspace_bytes",
     "pv_pages_gather", "pv_pages_scatter", "pv_cost_model", "pv_retention_order",
     "pv_rope_kv_append_planned", "pv_rope_table",
+    "pv_multi_token_paged_attn_noalloc", "pv_static_scratch_bytes",
 ]
 
 
@@ -104,6 +105,10 @@ _lib.pv_kv_append_planned.argtypes = [_vp] * 7
 _lib.pv_multi_token_paged_attn_planned.restype = ctypes.c_int
 _lib.pv_multi_token_paged_attn_planned.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp,
                                                    _vp, ctypes.c_size_t, _vp]
+_lib.pv_multi_token_paged_attn_noalloc.restype = ctypes.c_int
+_lib.pv_multi_token_paged_attn_noalloc.argtypes = [_vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp]
+_lib.pv_static_scratch_bytes.restype = ctypes.c_size_t
+_lib.pv_static_scratch_bytes.argtypes = []
 _lib.pv_kv_append.restype = ctypes.c_int
 _lib.pv_kv_append.argtypes = [_descp, _vp, _vp, _vp, ctypes.c_int32, _i32p, _i32p, _i32p,
                               ctypes.c_int32, ctypes.c_int32, _vp, _vp, _vp]
@@ -336,6 +341,17 @@ def multi_token_paged_attn_planned(plan: Plan, q, k_pages, v_pages, page_table, 
         plan.handle, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), float(scale),
         _ptr(out), _ptr(workspace), _nbytes(workspace), _stream(stream)),
         "pv_multi_token_paged_attn_planned")
+
+
+def multi_token_paged_attn_noalloc(plan: Plan, q, k_pages, v_pages, page_table, scale: float, out,
+                                   stream=None):
+    _check(_lib.pv_multi_token_paged_attn_noalloc(
+        plan.handle, _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(page_table), float(scale),
+        _ptr(out), _stream(stream)), "pv_multi_token_paged_attn_noalloc")
+
+
+def static_scratch_bytes() -> int:
+    return int(_lib.pv_static_scratch_bytes())
 
 
 def kv_append(desc: PoolDesc, k_new, v_new, page_table, max_pages_per_req: int, slot_offsets,

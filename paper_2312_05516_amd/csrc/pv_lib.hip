@@ -264,6 +264,60 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
                        static_cast<hipStream_t>(stream));
 }
 
+// ---------------------------------------------------------------------------------------------
+// The launch that allocates nothing: everything the library itself would need device memory for
+// (the plan's lists, the partial results of split KV ranges) lives in one static array.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kScratchBytes = PV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];  // per device: the address of that device's copy
+
+// address of the current device's scratch array (looked up once per device, then kept)
+static pv_status scratch_base(unsigned char **base)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return PV_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PV_ERR_UNSUPPORTED;
+    void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PV_ERR_HIP;
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);  // same value from any thread
+    }
+    *base = static_cast<unsigned char *>(p);
+    return PV_OK;
+}
+
+size_t pv_static_scratch_bytes(void) { return kScratchBytes; }
+
+pv_status pv_multi_token_paged_attn_noalloc(pv_plan *plan, const void *q, const void *k_pages,
+                                            const void *v_pages, const int32_t *page_table,
+                                            float scale, void *out, void *stream)
+{
+    if (!plan) return PV_ERR_INVALID_ARG;
+    if (plan->total_q == 0) return PV_OK;
+    pv_status s = attn_args_ok(plan, q, k_pages, v_pages, page_table, scale, out);
+    if (s != PV_OK) return s;
+    const size_t lists = pv::align_up(plan->image.size(), 256);
+    if (lists + plan->workspace_bytes > kScratchBytes) return PV_ERR_WORKSPACE;  // batch too large
+    unsigned char *base = nullptr;
+    s = scratch_base(&base);
+    if (s != PV_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Nothing in the array has to start at zero: the lists are overwritten whole, and every
+    // partial-result slot is written by the attention kernels before the merge reads it.
+    if (hipMemcpyAsync(base, plan->image.data(), plan->image.size(), hipMemcpyHostToDevice, st) !=
+        hipSuccess)
+        return PV_ERR_HIP;
+    float *ws_o = nullptr, *ws_ml = nullptr;
+    if (plan->workspace_bytes > 0) {
+        ws_o = reinterpret_cast<float *>(base + lists);
+        ws_ml = ws_o + (size_t)plan->partial_slots * plan->pool.head_dim;
+    }
+    return attn_launch(plan, pv::lists_at(plan, base), q, k_pages, v_pages, page_table, scale, out,
+                       ws_o, ws_ml, st);
+}
+
 static pv_status check_prefix(const int32_t *q_lens, const int32_t *q_start, int32_t num_reqs,
                               int32_t total_q)
 {
