@@ -444,7 +444,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         nxt[u][v] += shift;  // block b+1's exponents follow the new reference
-                        cinit[u][v] = -mc[u];
+                        cinit[u][v] += shift;  // = -mc[u], updated in place (no register move)
                     }
                     thr_rel[u] = thr[u] - mc[u];
                 }
