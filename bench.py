@@ -191,14 +191,17 @@ class DeviceBatch:
                 "tflops_at_median": round(self.b.flops() / float(np.median(ms)) / 1e9, 2),
                 "kv_gbps_at_median": round(self.b.kv_bytes() / float(np.median(ms)) / 1e6, 1)}
 
-    def kernel_times(self, steps: int) -> dict:
-        """Average duration of each kernel over `steps` instrumented steps (HIP events recorded by
-        the library on the launch stream around every kernel)."""
+    def kernel_times(self, samples: int, burst: int = 8) -> dict:
+        """Average duration of each kernel (HIP events recorded by the library on the launch
+        stream around every kernel).  The plan keeps one pair of events per kernel, so a sample is
+        the last step of a burst of back-to-back steps: the kernels are measured in the same
+        busy state as in the timed loop, not after an idle gap."""
         pv = self.pv
         pv.plan_enable_timing(self.plan, True)
         acc = {k: [] for k in KERNEL_NAMES}
-        for i in range(steps):
-            self.step(i)
+        for s in range(samples):
+            for i in range(burst):
+                self.step(s * burst + i)
             for k in KERNEL_NAMES:
                 ms = pv.plan_kernel_ms(self.plan, k)
                 if ms >= 0:
@@ -360,7 +363,7 @@ def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool
     db = DeviceBatch(b, layers, serial, use_graph)
     ms = db.time_steps(steps, warmup)
     sustained = db.sustained(sustained_seconds) if sustained_seconds > 0 else None
-    ktimes = db.kernel_times(50)
+    ktimes = db.kernel_times(30)
     roof = roofline_for(db, ktimes)
     res = {
         "workload": name,

@@ -328,7 +328,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     //                unless PRE, exp2 one slot later, pack to 16 bits one slot after that);
     //   slots 16-31  value product of block b (V operand (slot-16)/2, sub-tile slot%2; every P
     //                operand is complete when its instruction issues), the V operands requested
-    //                six slots ahead of their use; in between the copy of block b+PF (slots 16-19), the
+    //                six slots ahead of their use; in between the copy of block b+PF (its four
+    //                pieces spread over slots 16-20 and 29-32), the
     //                page ids of the next copy, from slot 20 on the maximum of block b+1's results
     //                (its last score instruction issued in slot 15, see mfma32_first); K operands
     //                are requested six slots ahead of their use as well, those of the next
@@ -345,6 +346,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         u32x4 praw[SUB][2];
         float xs[SUB * 8][2], es[SUB * 8][2];
         float mx[SUB];
+        uint64_t dma_off[2];
+        const unsigned char *dma_src[LOADS];
 #pragma unroll
         for (int slot = 0; slot < 32; ++slot) {
             // --- the slot's matrix-core instruction
@@ -408,8 +411,22 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                 }
             }
             // --- copy of block b+PF (b + PF < nblocks inside the pipelined loop), one piece a slot
-            if (slot >= 16 && slot < 16 + LOADS) dma_piece(b + PF, id0, id1, slot - 16);
-            if (slot == 16 + LOADS) page_ids(b + PF + 1, id0, id1);
+            // (the scalar address arithmetic of a piece goes one slot ahead of its copy, into
+            // slots that have no operand read, so that no slot carries more than about five
+            // instructions next to its matrix-core instruction)
+            if (slot == 16) {
+                dma_off[0] = (uint64_t)(uint32_t)id0 * page_bytes;
+                dma_off[1] = (uint64_t)(uint32_t)id1 * page_bytes;
+            }
+            if (slot == 17 || slot == 19 || slot == 29 || slot == 31) {
+                const int i = slot < 20 ? (slot - 17) / 2 : 2 + (slot - 29) / 2;
+                dma_src[i] = ((i & 2) ? v_src : k_src) + dma_off[i & 1];
+            }
+            if (slot == 18 || slot == 20 || slot == 30) {
+                const int i = slot < 21 ? (slot - 18) / 2 : 2;
+                lds_dma16(dma_src[i], lane_bytes, smem[(b + PF) % STAGES] + (w + 4 * i) * 1024);
+            }
+            if (slot == 21) page_ids(b + PF + 1, id0, id1);
             // --- maximum of block b+1's results, two registers per slot and sub-tile
             if (slot >= 20 && slot < 28) {
                 const int i = slot - 20;
@@ -419,6 +436,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        lds_dma16(dma_src[3], lane_bytes, smem[(b + PF) % STAGES] + (w + 4 * 3) * 1024);
         // --- row sums of what the matrix cores saw, in one cluster
 #pragma unroll
         for (int u = 0; u < SUB; ++u) {
