@@ -284,24 +284,19 @@ def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
             "frac": round(ach / MFMA_PEAK_TFLOPS, 4), **common}
 
 
-def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
-    """Time the CPU oracle (fp64, as it stands) on a bounded sample of (request, KV head) units of
-    the same workload, on the host cores of this machine."""
+def _oracle_sample(db: DeviceBatch, budget_flops: float, threads: int):
+    """Run the oracle on a stratified sample of (request, KV head) units worth about budget_flops.
+    Returns (flops done, seconds, units, stride, threads used)."""
     import torch
     import oracle
     b = db.b
-    oracle.build()
     Hq, Hkv, D = b.num_q_heads, b.num_kv_heads, b.head_dim
-    threads = len(os.sched_getaffinity(0))
-    threads = int(os.environ.get("OMP_NUM_THREADS", threads) or threads)
-    # assumed oracle speed, for sizing the sample only: ~4 GFLOP/s per thread in fp64
-    budget_flops = target_seconds * 4e9 * threads
     G = Hq // Hkv
     c = b.ctx_lens.astype(np.int64)
     n = b.q_lens.astype(np.int64)
     unit_flops = 4 * D * G * (n * c + n * (n + 1) // 2)  # per (request, KV head)
     # stratified sample: the (request, KV head) units sorted by cost, every k-th of them (KV head
-    # chosen by a seeded draw), k such that the sample fits the budget; at least one unit
+    # order by a seeded draw), k such that the sample fits the budget; at least one unit
     rng = np.random.default_rng(b.seed + 99)
     live = [r for r in np.argsort(unit_flops, kind="stable") if n[r] > 0]
     all_units = [(int(r), int(h)) for r in live for h in rng.permutation(Hkv)]
@@ -348,12 +343,34 @@ def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
     _, info = oracle.attn(pool, Hq, q_s, sub_k, sub_v, sub_table, b.ctx_lens[reqs], ql, qs, b.scale,
                           unit_mask=mask[reqs], num_threads=threads)
     dt = time.perf_counter() - t0
-    units = int(mask.sum())
-    return {"value": round(total / dt / 1e12, 6), "unit": "TFLOP/s", "cores": info["threads"],
+    return total, dt, int(mask.sum()), stride, info["threads"]
+
+
+def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
+    """Time the CPU oracle (fp64, as it stands) on a bounded sample of (request, KV head) units of
+    the same workload, on the host cores of this machine.  A small pilot sample measures how fast the
+    oracle is on this workload (generation batches are memory-bound on the CPU too); the reported
+    sample is then sized for about target_seconds."""
+    import oracle
+    b = db.b
+    oracle.build()
+    threads = len(os.sched_getaffinity(0))
+    threads = int(os.environ.get("OMP_NUM_THREADS", threads) or threads)
+    # assumed oracle speed, for sizing the sample only: ~4 GFLOP/s per thread in fp64.  Batches of
+    # generation steps (a few rows per unit) are memory-bound on the CPU too: there a pilot sample
+    # (a twentieth of the time) measures the speed first.
+    speed = 4e9 * threads
+    live = b.q_lens > 0
+    rows_per_unit = float(b.q_lens[live].mean()) * b.num_q_heads / b.num_kv_heads if live.any() else 0
+    if rows_per_unit < 16:
+        done, dt, _, _, _ = _oracle_sample(db, target_seconds / 20 * speed, threads)
+        speed = done / max(dt, 1e-6)
+    total, dt, units, stride, used = _oracle_sample(db, target_seconds * speed, threads)
+    return {"value": round(total / dt / 1e12, 6), "unit": "TFLOP/s", "cores": used,
             "kind": "oracle", "seconds": round(dt, 2),
-            "sample": f"{units} of {b.num_reqs * Hkv} (request, KV head) units of {b.name} "
-                      f"(every {stride}-th unit in order of cost), {total / 1e9:.2f} GFLOP, "
-                      f"fp64 C oracle with OpenMP, attention only"}
+            "sample": f"{units} of {b.num_reqs * b.num_kv_heads} (request, KV head) units of "
+                      f"{b.name} (every {stride}-th unit in order of cost), {total / 1e9:.2f} "
+                      f"GFLOP, fp64 C oracle with OpenMP, attention only"}
 
 
 def run_workload(name: str, steps: int, warmup: int, layers: int, with_cpu: bool,
