@@ -286,7 +286,7 @@ def roofline_for(db: DeviceBatch, ktimes: dict) -> dict:
 
 def _oracle_sample(db: DeviceBatch, budget_flops: float, threads: int):
     """Run the oracle on a stratified sample of (request, KV head) units worth about budget_flops.
-    Returns (flops done, seconds, units, stride, threads used)."""
+    Returns (flops done, seconds, units, how they were picked, threads used)."""
     import torch
     import oracle
     b = db.b
@@ -304,13 +304,23 @@ def _oracle_sample(db: DeviceBatch, budget_flops: float, threads: int):
     total_all = sum(int(unit_flops[r]) for r, _ in all_units)
     stride = max(1, int(np.ceil(total_all / max(budget_flops, 1.0))))
     page_bytes = 2 * Hkv * b.page_size * D * 2  # K and V image of one page, all KV heads
-    while True:  # the sampled requests' pages are copied to the host: keep that under 4 GB
-        picked = all_units[stride // 2::stride] or all_units[:1]
-        host_bytes = sum(int(np.ceil(b.kv_lens[r] / b.page_size)) * page_bytes
-                         for r in {r for r, _ in picked})
-        if host_bytes <= 4e9 or len(picked) == 1:
-            break
-        stride *= 2
+
+    def host_bytes(units):
+        return sum(int(np.ceil(b.kv_lens[r] / b.page_size)) * page_bytes for r in {r for r, _ in units})
+
+    picked = all_units[stride // 2::stride] or all_units[:1]
+    how = f"every {stride}-th unit in order of cost"
+    if host_bytes(picked) > 4e9 and len(picked) > 1:
+        # the sampled requests' pages are copied to the host; a request's pages hold all its KV
+        # heads, so where that copy would pass 4 GB take whole requests instead: every k-th request
+        # in order of cost with all its KV heads
+        k = max(1, int(np.ceil(stride / Hkv)))
+        while True:
+            picked = [(int(r), h) for r in live[k // 2::k] for h in range(Hkv)]
+            if host_bytes(picked) <= 4e9 or len(picked) <= Hkv:
+                break
+            k += max(1, k // 4)
+        how = f"all KV heads of every {k}-th request in order of cost (host copy kept under 4 GB)"
     mask = np.zeros((b.num_reqs, Hkv), dtype=np.uint8)
     total = 0
     for r, h in picked:
@@ -343,7 +353,7 @@ def _oracle_sample(db: DeviceBatch, budget_flops: float, threads: int):
     _, info = oracle.attn(pool, Hq, q_s, sub_k, sub_v, sub_table, b.ctx_lens[reqs], ql, qs, b.scale,
                           unit_mask=mask[reqs], num_threads=threads)
     dt = time.perf_counter() - t0
-    return total, dt, int(mask.sum()), stride, info["threads"]
+    return total, dt, int(mask.sum()), how, info["threads"]
 
 
 def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
@@ -365,11 +375,11 @@ def cpu_baseline(db: DeviceBatch, target_seconds: float) -> dict:
     if rows_per_unit < 16:
         done, dt, _, _, _ = _oracle_sample(db, target_seconds / 20 * speed, threads)
         speed = done / max(dt, 1e-6)
-    total, dt, units, stride, used = _oracle_sample(db, target_seconds * speed, threads)
+    total, dt, units, how, used = _oracle_sample(db, target_seconds * speed, threads)
     return {"value": round(total / dt / 1e12, 6), "unit": "TFLOP/s", "cores": used,
             "kind": "oracle", "seconds": round(dt, 2),
             "sample": f"{units} of {b.num_reqs * b.num_kv_heads} (request, KV head) units of "
-                      f"{b.name} (every {stride}-th unit in order of cost), {total / 1e9:.2f} "
+                      f"{b.name} ({how}), {total / 1e9:.2f} "
                       f"GFLOP, fp64 C oracle with OpenMP, attention only"}
 
 
