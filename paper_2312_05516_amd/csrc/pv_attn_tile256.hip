@@ -410,7 +410,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                     praw[j / 8][(j % 8) / 4][j % 4] = T::pack2(es[j][0], es[j][1]);
                 }
             }
-            // --- copy of block b+PF (b + PF < nblocks inside the pipelined loop), one piece a slot
+            // --- copy of block b+PF (of the last block again once b + PF >= nblocks: page_ids
+            // clamps the block number), one piece a slot
             // (the scalar address arithmetic of a piece goes one slot ahead of its copy, into
             // slots that have no operand read, so that no slot carries more than about five
             // instructions next to its matrix-core instruction)
@@ -474,10 +475,10 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         publish(true);
     };
 
-    // blocks 0 .. nfast are unmasked for every row of this wavefront, and every pipelined
-    // iteration still has a copy to issue
+    // blocks 0 .. nfast are unmasked for every row of this wavefront.  Near the end of the item a
+    // pipelined iteration has no further block to copy: it fetches the last block once more, into
+    // a stage nobody reads again, so that the count of copies in flight stays what the waits assume
     int nfast = (unmasked_end - it.kv_begin) / BK - 1;
-    if (nfast > nblocks - PF) nfast = nblocks - PF;
     if (nfast < 0) nfast = 0;
     nfast &= ~1;  // pairs: the results ping-pong between two register sets without copies
 
