@@ -22,8 +22,10 @@
  *     before anything is launched.  The *contents* of device index arrays are
  *     not checked by the launching calls; pv_plan_check_page_table() checks a
  *     host copy.
- *   - The library keeps no global state and allocates device memory in two documented places only
- *     (pv_plan_upload; the one-shot forms when the workspace passed is too small for the lists).
+ *   - The library allocates device memory in two documented places only (pv_plan_upload; the
+ *     one-shot forms when the workspace passed is too small for the lists).  Its only state
+ *     outside plans is the static device array of pv_multi_token_paged_attn_noalloc and the
+ *     address of that array on each GPU, looked up once.
  *   - A plan may be shared by the launches of many layers, but by one host thread at a time (a
  *     launch updates the plan's timing state).
  *   - Alignment: q, out, k_new, v_new, the pools and the rotary table are read and written with

@@ -27,9 +27,19 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# kernels with pinned matrix-core instructions: their generated code is kept and scanned (isa_check)
+ISA_CHECKED = ["pv_attn_tile256.hip"]
+
+
+def isa_path(src: str) -> str:
+    return os.path.join(OBJ, os.path.splitext(src)[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+
+
 def _compile(src: str, extra) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc()] + FLAGS + list(extra) + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    keep = ["-save-temps=obj"] if src in ISA_CHECKED else []
+    cmd = ([_hipcc()] + FLAGS + keep + list(extra)
+           + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj])
     r = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (r.stdout + r.stderr).splitlines()
                      if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
@@ -37,6 +47,19 @@ def _compile(src: str, extra) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n{msgs}")
     if msgs.strip():
         print(msgs, file=sys.stderr)
+    if src in ISA_CHECKED:
+        try:
+            from . import isa_check
+        except ImportError:  # run as a script: the module sits beside this file
+            import isa_check
+        with open(isa_path(src)) as f:
+            pinned, hazards = isa_check.pinned_mfma_hazards(f.read())
+        if pinned == 0 or hazards:
+            raise RuntimeError(f"{src}: {pinned} pinned matrix-core instructions, "
+                               f"{len(hazards)} read a register written less than two "
+                               "instructions earlier:\n"
+                               + "\n".join(f"  line {a}: {b}\n    <- line {c}: {d}"
+                                           for a, b, c, d in hazards[:10]))
     return obj
 
 

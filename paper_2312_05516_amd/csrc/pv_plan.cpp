@@ -397,7 +397,7 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
         return PV_ERR_OUT_OF_RANGE;
     }
     order_items(plan->narrow, kNarrowRows, tune.xcds);
-    order_items(plan->wide, env_int("PV_WIDE_COST_ROWS", kWideRows), tune.xcds);
+    order_items(plan->wide, kWideRows, tune.xcds);
     order_items(plan->tile256, kTileRows, tune.xcds);
     plan->partial_slots = slots;
     for (size_t i = 0; i < plan->combine.size(); ++i)
