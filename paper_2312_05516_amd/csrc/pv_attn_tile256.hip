@@ -22,8 +22,9 @@
 //      - for the usual small scales the queries are pre-multiplied by scale*log2(e) once (rounded
 //        to the 16-bit type; see PRE below) and the score product starts from minus the row's
 //        reference maximum instead of zero, so a probability is one exp2 of a matrix-core result;
-//      - row sums use v_dot2 on the packed probabilities, but all sixteen at the end of the
-//        iteration: a dot instruction waits for the matrix pipe to drain, once per cluster;
+//      - row sums are plain additions of the exponentials, spread over the slots of the value
+//        product (a v_dot2 on the packed probabilities would halve their number, but a dot
+//        instruction waits for the matrix pipe to drain);
 //      - addresses of the asynchronous copies are two scalar multiplies and four 64-bit adds.
 //  * K/V page tiles go HBM/L2 -> LDS directly (global_load_lds) into a ring of 8 stages, six blocks
 //    ahead; one s_barrier per block.  K operands of block b+2 are requested before the barrier at
@@ -334,8 +335,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     //                (its last score instruction issued in slot 15, see mfma32_first); K operands
     //                are requested six slots ahead of their use as well, those of the next
     //                iteration's first three k-steps in slots 26-30;
-    //   then the sixteen row-sum dot products in one cluster, the test for a reference update,
-    //   and the barrier.
+    //                the 32 additions of the row sums fill what room the slots 16-31 have left;
+    //   then the test for a reference update, and the barrier.
     f32x16 cinit[SUB];
     float thr_rel[SUB];  // PRE: threshold for block maxima that are relative to the reference
     auto fast_step = [&](int b, const f32x16 (&cur)[SUB], f32x16 (&nxt)[SUB]) {
@@ -346,8 +347,12 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         u32x4 praw[SUB][2];
         float xs[SUB * 8][2], es[SUB * 8][2];
         float mx[SUB];
+        float psum[SUB] = {0.f, 0.f};
         uint64_t dma_off[2];
         const unsigned char *dma_src[LOADS];
+        // how many of the 32 row-sum additions each of the slots 16-31 takes: as many as fit
+        // beside what the slot already carries
+        constexpr int kSumAdds[16] = {0, 3, 1, 3, 0, 0, 2, 3, 2, 3, 2, 3, 3, 3, 1, 3};
 #pragma unroll
         for (int slot = 0; slot < 32; ++slot) {
             // --- the slot's matrix-core instruction
@@ -435,19 +440,23 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                 for (int u = 0; u < SUB; ++u)
                     mx[u] = max3_raw(i == 0 ? nxt[u][0] : mx[u], nxt[u][2 * i], nxt[u][2 * i + 1]);
             }
+            // --- row sums: plain additions of the exponentials (before their rounding to 16
+            // bits), spread over the slots of the value product
+            if (slot >= 16) {
+                int first = 0;
+#pragma unroll
+                for (int t = 16; t < slot; ++t) first += kSumAdds[t - 16];
+#pragma unroll
+                for (int a = 0; a < kSumAdds[slot - 16]; ++a) {
+                    const int k = first + a;
+                    psum[k / 16] += es[k / 2][k % 2];
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         lds_dma16(dma_src[3], lane_bytes, smem[(b + PF) % STAGES] + (w + 4 * 3) * 1024);
-        // --- row sums of what the matrix cores saw, in one cluster
 #pragma unroll
-        for (int u = 0; u < SUB; ++u) {
-            float psum = 0.f;
-#pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) psum = T::add_pair(praw[u][pg][jj], psum);
-            l_run[u] += psum;
-        }
+        for (int u = 0; u < SUB; ++u) l_run[u] += psum[u];
         if constexpr (PRE) {
             if (__any(mx[0] > thr_rel[0] || mx[1] > thr_rel[1])) {
                 float mx_abs[SUB], mc_old[SUB];
