@@ -299,7 +299,8 @@ def test_full_size_long_history(oracle):
     _full_size_parity(oracle, b, [int(order[0]), int(order[-1])], [3])
 
 
-@pytest.mark.parametrize("kernels", ["one_attention_kernel", "two_attention_kernels"])
+@pytest.mark.parametrize("kernels", ["one_attention_kernel", "two_attention_kernels",
+                                     "with_256_row_kernel"])
 def test_graph_replay_matches_eager(oracle, kernels, monkeypatch):
     """The planned calls of a mixed batch (append, attention, the merge) captured into one HIP
     graph: every replay must reproduce the eager result bit for bit, with eager work and
@@ -312,12 +313,16 @@ def test_graph_replay_matches_eager(oracle, kernels, monkeypatch):
                   head_dim=128, dtype="bf16", seed=61)
     if kernels == "two_attention_kernels":
         monkeypatch.setenv("PV_UNIFY_MAX_STEPS", "10")
+    if kernels == "with_256_row_kernel":  # the 150-token request: 600 rows = two 256-row tiles + rest
+        monkeypatch.setenv("PV_TILE_MIN_KEYS", "128")
     case = H.make_case(b, fill="nan")
     desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
     plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
     pv.plan_upload(plan)
     if kernels == "one_attention_kernel":
         assert pv.plan_num_work_items(plan, 0) == 0 and pv.plan_num_work_items(plan, 1) > 0
+    elif kernels == "with_256_row_kernel":
+        assert pv.plan_num_work_items(plan, 3) >= 4 and pv.plan_num_work_items(plan, 1) > 0
     else:
         assert pv.plan_num_work_items(plan, 0) > 0 and pv.plan_num_work_items(plan, 1) > 0
     assert pv.plan_num_work_items(plan, 2) > 0

@@ -94,3 +94,36 @@ def test_tile256_large_scale_and_page_permutation(oracle):
     base, _, _ = H.gpu_run(case)
     moved, _, _ = H.gpu_run(case, page_table=table, pools=(kp, vp))
     assert np.array_equal(base, moved)
+
+
+@pytest.mark.parametrize("scale", [-0.125, 0.0, 0.2, 0.5])
+def test_tile256_scales_on_both_sides_of_the_prescaling_limit(oracle, scale):
+    """|scale*log2(e)| <= 0.25 takes the instantiation with pre-multiplied queries (negative
+    scales included: the sign travels with the queries; zero gives uniform weights), larger scales
+    the one that scales in fp32."""
+    b = wl.custom([2100, 2300], [40, 32], num_q_heads=8, num_kv_heads=1, head_dim=128,
+                  dtype="bf16", seed=71, value_std=0.5)
+    items, _ = _tile_items(b)
+    assert items
+    case = H.make_case(b, fill="nan")
+    got, _, _ = H.gpu_run(case, scale=scale)
+    from test_gpu_parity import oracle_out
+    want = oracle_out(oracle, case, scale=scale)
+    got = H.bits_to_f64(got, b.dtype)
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max()
+    print(f"scale {scale}: max abs err {err:.3e}", flush=True)
+    assert err <= H.TOL[b.dtype]
+
+
+def test_tile256_range_longer_than_the_page_id_staging_is_cut(oracle, monkeypatch):
+    """An item's page ids are staged in LDS, 8192 at most: a KV range of 140 K keys (8750 pages)
+    is cut in two even when the plan would otherwise leave it whole (split target 1), and the
+    parts are merged."""
+    monkeypatch.setenv("PV_SPLIT_TARGET", "1")
+    b = wl.custom([140000 - 32], [32], num_q_heads=8, num_kv_heads=1, head_dim=128, dtype="bf16",
+                  seed=73)
+    items, _ = _tile_items(b)
+    assert items and all(int(it[5] - it[4]) <= 8192 * 16 for it in items)
+    assert len(items) == 2 and all(int(it[7]) == 2 for it in items)
+    check_case(oracle, H.make_case(b, fill="nan"))
