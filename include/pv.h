@@ -191,8 +191,12 @@ pv_status pv_kv_append_planned(pv_plan *plan, const void *k_new, const void *v_n
  *   s_t = scale * <q[q_start[r]+i, hq, :], K_r[t, hk, :]>     for t = 0 .. ctx_lens[r]+i
  *   out[q_start[r]+i, hq, :] = sum_t softmax(s)_t * V_r[t, hk, :]
  * with K_r, V_r read through the page table.  `scale` multiplies the scores (the paper's
- * divisor is its reciprocal; 1/sqrt(D) is customary).  Scores, softmax and the weighted sum
- * are accumulated in fp32; out is rounded to the 16-bit dtype.  Must run after the append of
+ * divisor is its reciprocal; 1/sqrt(D) is customary) and may be any finite number, negative
+ * and zero included; NaN or infinity returns PV_ERR_INVALID_ARG.  Scores, softmax and the
+ * weighted sum are accumulated in fp32; out is rounded to the 16-bit dtype.  For
+ * |scale*log2(e)| <= 0.25 the 256-row kernel applies the scale to the queries (rounded back to
+ * 16 bits) instead of the scores, a perturbation of the size of the rounding the probabilities
+ * get; larger scales are applied to the scores in fp32 by every kernel.  Must run after the append of
  * the same batch on the same stream.
  *   q, out     : device [total_q, Hq, D]
  * Launches at most four kernels (the two matrix-core attention kernels, bandwidth-oriented

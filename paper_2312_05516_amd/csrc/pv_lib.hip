@@ -1,6 +1,7 @@
 // C ABI entry points that touch the GPU: plan upload, the planned launches and the one-shot forms.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -185,7 +186,7 @@ static pv_status attn_args_ok(const pv_plan *plan, const void *q, const void *k_
     if (!pv::aligned16(q) || !pv::aligned16(k_pages) || !pv::aligned16(v_pages) ||
         !pv::aligned16(out))
         return PV_ERR_INVALID_ARG;
-    if (!(scale == scale)) return PV_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return PV_ERR_INVALID_ARG;
     (void)plan;
     return PV_OK;
 }
