@@ -2,13 +2,17 @@
 """Benchmark of the multi-token paged attention hot path on one MI355X.
 
 One "step" = one pass of the whole hot path over one batch, as one transformer layer would run
-it: KV append of the batch's new tokens, then multi-token paged attention (both attention
-kernels and the split-KV merge).  The per-batch plan (prefix sums, work lists) is built once on
+it: KV append of the batch's new tokens, then multi-token paged attention (whichever of the
+three attention kernels and the split-KV merge the batch needs).  The per-batch plan (prefix sums, work lists) is built once on
 the CPU and reused by every step, as the paper does across layers (Section 6.4); its cost is
 reported separately.  Every step uses the next of several independent KV pools ("layers") so the
 data comes from HBM, not from a cache warmed by the previous step.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.  The headline workload is the largest single-GPU configuration
+(long_history); `other_workloads` carries the same record for the other configurations.  Per
+workload: the timed loop (--steps after --warmup), a `sustained` loop of at least 0.5 s with
+median and minimum per step, the `roofline` of the dominant attention kernel from the library's
+own per-kernel events, and `cpu_baseline`, the CPU oracle timed on a stated sample.
 """
 from __future__ import annotations
 
@@ -41,7 +45,8 @@ def parse_args():
     ap.add_argument("--workload", default="long_history",
                     help="tiny | mha13b | gqa70b | long_history | decode_heavy | micro_c<ctx>")
     ap.add_argument("--layers", type=int, default=0, help="independent KV pools cycled through "
-                    "(0 = pick so that the pools exceed 1 GiB of KV, at most 8)")
+                    "(0 = pick: at least four, two for pools of 4 GiB of KV and more, enough to "
+                    "exceed 1 GiB of KV, at most 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="target CPU time of the oracle sample of the headline workload (the other "
@@ -99,7 +104,10 @@ class DeviceBatch:
         page_elems = Hkv * b.page_size * D
         pool_bytes = 2 * b.num_pages * page_elems * 2  # K + V
         if layers <= 0:
-            layers = int(min(8, max(2, np.ceil((1 << 30) / max(b.kv_bytes(), 1)))))
+            # at least four independent pools unless one pool alone is far beyond every cache
+            # (the chip's last-level cache is 256 MB): every step then reads its KV from HBM
+            few = 2 if b.kv_bytes() >= (4 << 30) else 4
+            layers = int(min(8, max(few, np.ceil((1 << 30) / max(b.kv_bytes(), 1)))))
             free, _ = torch.cuda.mem_get_info()
             layers = int(max(1, min(layers, (free * 0.6) // pool_bytes)))
         self.layers = layers
