@@ -646,12 +646,12 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the attention shards "
-              "by KV head or by request with no exchange; see DESIGN.md). Run with --gpus 1.",
+              "by KV head or by request with no exchange). Run with --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
-        print("bench.py needs a GPU (run it under gpurun)", file=sys.stderr)
+        print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     if args.microbench:
         print(json.dumps({"metric": "attention call time on the paper's kernel-figure shape "

@@ -11,7 +11,7 @@ if os.path.dirname(os.path.abspath(__file__)) not in sys.path:
 
 
 def pytest_configure(config):
-    config.addinivalue_line("markers", "gpu: needs a real MI355X (run under gpurun)")
+    config.addinivalue_line("markers", "gpu: needs a real MI355X")
 
 
 @pytest.fixture(scope="session")
