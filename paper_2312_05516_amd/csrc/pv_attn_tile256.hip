@@ -133,12 +133,17 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     for (int i = (int)threadIdx.x; i < 2 * nblocks && i < kTileMaxPages; i += 256)
         page_lds[i] = pt[pg0 + i <= last_pg ? pg0 + i : last_pg];
     __syncthreads();
-    auto page_ids = [&](int b, int &id0, int &id1) {
+    // in two steps, so that the pipelined loop can put other work between the LDS read and the
+    // first use of its result
+    auto page_ids_request = [&](int b) {
         const int bb = b < nblocks ? b : nblocks - 1;  // ids past the last block are never used
-        const u32x2 ids = *reinterpret_cast<const u32x2 *>(&page_lds[2 * bb]);
+        return *reinterpret_cast<const u32x2 *>(&page_lds[2 * bb]);
+    };
+    auto page_ids_take = [&](u32x2 ids, int &id0, int &id1) {
         id0 = __builtin_amdgcn_readfirstlane((int)ids[0]);
         id1 = __builtin_amdgcn_readfirstlane((int)ids[1]);
     };
+    auto page_ids = [&](int b, int &id0, int &id1) { page_ids_take(page_ids_request(b), id0, id1); };
     // Asynchronous copy of block b into stage b % STAGES.  The stage is 16 pieces of 1 KiB: K page
     // 0, K page 1, V page 0, V page 1, four pieces each; wavefront w moves piece w of each, i.e. the
     // bytes [w KiB, w KiB + 1 KiB) of the (page, head) tile: source = pool + page id * page bytes
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
     //                operand is complete when its instruction issues), the V operands requested
     //                six slots ahead of their use; in between the copy of block b+PF (its four
     //                pieces spread over slots 16-20 and 29-32), the
-    //                page ids of the next copy, from slot 20 on the maximum of block b+1's results
+    //                page ids of the next copy (requested in slot 21, taken in slot 31), from slot 20 on the maximum of block b+1's results
     //                (its last score instruction issued in slot 15, see mfma32_first); K operands
     //                are requested six slots ahead of their use as well, those of the next
     //                iteration's first three k-steps in slots 26-30;
@@ -350,6 +355,7 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
         float psum[SUB] = {0.f, 0.f};
         uint64_t dma_off[2];
         const unsigned char *dma_src[LOADS];
+        u32x2 next_ids;
         // how many of the 32 row-sum additions each of the slots 16-31 takes: as many as fit
         // beside what the slot already carries
         constexpr int kSumAdds[16] = {0, 3, 1, 3, 0, 0, 2, 3, 2, 3, 2, 3, 3, 3, 1, 3};
@@ -373,6 +379,10 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                 const int pg = i / 4, blk = i % 4;
                 o[u][blk] = T::mfma32(as_vec8<T>(vf[pg][blk]), as_vec8<T>(praw[u][pg]), o[u][blk]);
             }
+            // the matrix-core instruction opens its slot: what follows runs beside it (left to
+            // itself the compiler puts every other slot's exponentials in front of it, and two
+            // slots' worth of them between two matrix-core instructions do not fit beside one)
+            __builtin_amdgcn_sched_barrier(0);
             // --- LDS reads: V operand i of this block six slots ahead of its first use (they
             //     take over the registers of K operands already consumed), later the K operands
             //     of block b+2
@@ -432,7 +442,8 @@ __global__ __launch_bounds__(256, 1) void attn_tile256_kernel(
                 const int i = slot < 21 ? (slot - 18) / 2 : 2;
                 lds_dma16(dma_src[i], lane_bytes, smem[(b + PF) % STAGES] + (w + 4 * i) * 1024);
             }
-            if (slot == 21) page_ids(b + PF + 1, id0, id1);
+            if (slot == 21) next_ids = page_ids_request(b + PF + 1);
+            if (slot == 31) page_ids_take(next_ids, id0, id1);
             // --- maximum of block b+1's results, two registers per slot and sub-tile
             if (slot >= 20 && slot < 28) {
                 const int i = slot - 20;
