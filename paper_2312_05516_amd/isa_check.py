@@ -54,3 +54,16 @@ def pinned_mfma_hazards(isa_text: str):
             if _regs(dest) & sources:
                 found.append((i + 1, ins, pi + 1, prev))
     return pinned, found
+
+
+def spill_counts(isa_text: str) -> dict:
+    """Kernel symbol -> vector-register spill count, from the metadata at the end of a .s file."""
+    out, name = {}, None
+    for line in isa_text.splitlines():
+        t = line.strip()
+        if t.startswith(".name:") and t.split(":", 1)[1].strip().startswith("_Z"):
+            name = t.split(":", 1)[1].strip()
+        elif t.startswith(".vgpr_spill_count:") and name is not None:
+            out[name] = int(t.split(":", 1)[1])
+            name = None
+    return out

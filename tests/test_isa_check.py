@@ -61,6 +61,11 @@ def test_the_kernel_as_built_has_pinned_instructions_and_no_hazard():
         if not os.path.exists(path):
             pv_build.build(verbose=False)  # keeps the generated code of these sources
         with open(path) as f:
-            pinned, hazards = isa_check.pinned_mfma_hazards(f.read())
+            text = f.read()
+        pinned, hazards = isa_check.pinned_mfma_hazards(text)
         assert pinned >= 64, f"{src}: the pipelined loops alone hold 64 pinned instructions"
         assert hazards == [], hazards[:5]
+        # a spill inside these loops is a vector-memory load whose wait also drains the
+        # asynchronous copies in flight: correct, but several times slower
+        spills = isa_check.spill_counts(text)
+        assert len(spills) == 4 and all(n == 0 for n in spills.values()), spills
