@@ -50,6 +50,7 @@ Tuning default_tuning()
     {
         const char *v = std::getenv("PV_TILE_MIN_KEYS");
         t.tile_min_keys = (v && *v == '0' && !v[1]) ? 0 : env_int("PV_TILE_MIN_KEYS", 8192);
+        t.tile_batch_min_keys = (v && *v) ? 0 : 1536;
     }
     return t;
 }
@@ -318,6 +319,36 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
     // bandwidth-oriented kernel is the better place for them.  Measured crossover on mixes of
     // 256-token prompts and generation steps over 2000-token contexts, MHA 40/40 and GQA 64/8 alike:
     // 80-100 K steps of 32 keys summed over the small units and KV heads (~1.5 GB of K/V).
+    // The 256-row kernel runs one workgroup per CU and needs a launch of its own, so in a mixed
+    // batch it only pays for long KV ranges (tile_min_keys).  A batch that is nearly all long
+    // multi-token units of head size 128 is another matter: measured on batches of 256- to 512-token
+    // requests it is ahead of the 128-row kernel from about 1.5 K keys up (+5 % there, +7-8 % with
+    // mixed lengths of 1-3.5 K or a few generation steps in the batch, +11 % at 4.5 K).  The
+    // lower limit applies when at least 90 % of the batch's (row, key) pairs are in full 256-row
+    // tiles of units that qualify under it, and those tiles are many enough and even enough that
+    // the plan will not cut them (a cut item writes fp32 partial results that a merge pass reads).
+    Tuning tune_batch = tune;
+    if (tune.tile_batch_min_keys > 0 && tune.tile_min_keys > tune.tile_batch_min_keys &&
+        pool->head_dim == 128) {
+        int64_t pairs_all = 0, pairs_tile = 0, items = 0, keys = 0, longest = 0;
+        for (int32_t r = 0; r < num_reqs; ++r) {
+            const int64_t n = q_lens[r], c = ctx_lens[r];
+            if (n == 0) continue;
+            const int64_t rows_total = n * G, kv = c + n;
+            pairs_all += rows_total * kv;
+            if (rows_total >= kTileRows && kv >= tune.tile_batch_min_keys) {
+                const int64_t tiles = rows_total / kTileRows;
+                pairs_tile += tiles * kTileRows * kv;
+                items += tiles * pool->num_kv_heads;
+                keys += tiles * pool->num_kv_heads * kv;
+                longest = std::max(longest, kv);
+            }
+        }
+        int64_t chunk = (keys + tune.split_target - 1) / std::max(tune.split_target, 1);
+        chunk = std::max<int64_t>(chunk, tune.min_split_keys);
+        if (items >= tune.split_target && pairs_tile * 10 >= pairs_all * 9 && longest <= 2 * chunk)
+            tune_batch.tile_min_keys = tune.tile_batch_min_keys;
+    }
     bool all_wide = false;
     if (tune.unify) {
         int64_t wide_steps = 0, small_steps = 0;
@@ -370,7 +401,7 @@ pv_status build_plan(const pv_pool_desc *pool, int32_t num_q_heads, const int32_
             const int32_t tile = use_wide ? kWideRows : kNarrowRows;
             // long units: their full 256-row tiles go to the 256-row kernel, the rest as usual
             int32_t rb = 0;
-            if (use_tile256(pool, tune, rows_total, (int64_t)c + n)) {
+            if (use_tile256(pool, tune_batch, rows_total, (int64_t)c + n)) {
                 for (; rb + kTileRows <= rows_total; rb += kTileRows) {
                     w.row_begin = rb;
                     w.row_count = kTileRows;

@@ -89,6 +89,9 @@ struct Tuning {
     int32_t tile_min_keys;   // (request, KV head) units with at least 256 rows and at least this
                              // many keys send their full 256-row tiles to the 256-row kernel
                              // (0 switches that kernel off)
+    int32_t tile_batch_min_keys;  // the lower limit that applies instead when nearly all of a
+                             // batch's work qualifies under it and its items need no splitting
+                             // (0: no such rule; it is off when tile_min_keys is set by hand)
 };
 
 }  // namespace pv

@@ -299,3 +299,38 @@ def test_cost_model_and_retention_order_match_the_oracle(pv, oracle):
     with pytest.raises(pv.PvError):
         pv.retention_order([1.0, 2.0], [3.0, 0.0])
     assert len(pv.retention_order([], [])) == 0
+
+
+def test_plan_sends_a_batch_of_long_multi_token_units_to_the_256_row_kernel(pv, monkeypatch):
+    """Units of at least 256 rows go to the 256-row kernel from 8192 keys up; from 1536 keys up
+    when nearly all of the batch qualifies and the plan has no reason to cut the items.  A limit
+    set by hand switches the batch rule off."""
+    from paper_2312_05516_amd import workloads as wl
+    monkeypatch.delenv("PV_TILE_MIN_KEYS", raising=False)
+    kw = dict(num_q_heads=64, num_kv_heads=8, head_dim=128, dtype="bf16", seed=5)
+
+    def counts(b):
+        desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+        plan = pv.plan_create(desc, b.num_q_heads, b.ctx_lens, b.q_lens, b.max_pages_per_req)
+        n = [pv.plan_num_work_items(plan, k) for k in (0, 1, 2, 3)]
+        plan.destroy()
+        return n
+
+    uniform = wl.custom([1024] * 16, [512] * 16, **kw)          # 1536 keys, 16 tiles x 8 heads each
+    assert counts(uniform) == [0, 0, 0, 2048]
+    short = wl.custom([600] * 16, [512] * 16, **kw)              # 1112 keys: below the batch limit
+    assert counts(short)[3] == 0
+    few = wl.custom([2048] * 4, [512] * 4, **kw)                 # 512 items: the plan would cut them
+    assert counts(few)[3] == 0
+    mixed = wl.custom([2048] * 16 + [3000] * 40, [512] * 16 + [1] * 40, **kw)
+    assert counts(mixed)[3] == 2048 and counts(mixed)[1] > 0     # a few generation steps: still
+    half = wl.custom([2048] * 16 + [30000] * 40, [512] * 16 + [16] * 40, **kw)
+    assert counts(half)[3] == 0                                  # most pairs elsewhere: not
+    outlier = wl.custom([1024] * 15 + [20000], [512] * 16, **kw)
+    n = counts(outlier)
+    assert n[3] > 0 and n[1] > 0                                 # only the long unit qualifies
+    for name in ("mha13b", "gqa70b"):
+        assert counts(wl.CONFIGS[name]())[3] == 0
+    assert counts(wl.CONFIGS["long_history"]())[3] == 1024
+    monkeypatch.setenv("PV_TILE_MIN_KEYS", "8192")
+    assert counts(uniform)[3] == 0

@@ -127,3 +127,16 @@ def test_tile256_range_longer_than_the_page_id_staging_is_cut(oracle, monkeypatc
     assert items and all(int(it[5] - it[4]) <= 8192 * 16 for it in items)
     assert len(items) == 2 and all(int(it[7]) == 2 for it in items)
     check_case(oracle, H.make_case(b, fill="nan"))
+
+
+def test_tile256_batch_of_medium_ranges_without_a_limit_set_by_hand(oracle, monkeypatch):
+    """With no limit in the environment, a batch whose work is nearly all in long multi-token
+    units goes to the 256-row kernel from 1536 keys up (here with the list length that counts as
+    long enough lowered to the size of the test)."""
+    monkeypatch.delenv("PV_TILE_MIN_KEYS")
+    monkeypatch.setenv("PV_SPLIT_TARGET", "16")
+    b = wl.custom([1500, 1700, 1600, 1900, 30], [64, 64, 96, 64, 1], num_q_heads=16,
+                  num_kv_heads=2, head_dim=128, dtype="bf16", seed=79)
+    items, rest = _tile_items(b)
+    assert len(items) == 2 * (2 + 2 + 3 + 2) and rest > 0
+    check_case(oracle, H.make_case(b, fill="nan"))
