@@ -249,11 +249,12 @@ pv_status pv_plan_kernel_ms(pv_plan *plan, int32_t kind, float *ms);
  * new token (normally ctx_lens[r]).
  *   pv_multi_token_paged_attn: when `workspace` (256-byte aligned) holds at least
  *     pv_attn_workspace_bytes(...) bytes, the temporary plan's lists go behind the partial results
- *     in it: nothing is allocated, the lists are copied with hipMemcpyAsync on `stream` and the
- *     library does not synchronise (the runtime returns from a copy out of pageable host memory
- *     once it has taken the bytes, which may include waiting for that one copy).  With a smaller
- *     workspace that still covers the partial results, the lists go to temporary device memory
- *     and the call waits for the stream before freeing it.
+ *     in it: nothing is allocated, the lists are copied with hipMemcpyAsync on `stream`, the
+ *     library does not synchronise, and the temporary plan is freed by a host function queued on
+ *     `stream` behind the launches (what the runtime does for a copy out of pageable host memory
+ *     is its own business; it may wait for that one copy).  With a smaller workspace that still
+ *     covers the partial results, the lists go to temporary device memory and the call waits for
+ *     the stream before freeing it.
  *   pv_kv_append has no buffer argument: temporary device memory, and it waits for the stream.
  */
 pv_status pv_kv_append(const pv_pool_desc *pool, const void *k_new, const void *v_new,

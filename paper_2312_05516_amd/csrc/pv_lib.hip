@@ -377,8 +377,9 @@ pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_head
     }
     // The caller's workspace holds the partial results first and, behind them, the plan's lists
     // when it is large enough for both (pv_attn_workspace_bytes is): then nothing is allocated
-    // and the call returns without waiting (the copy of the lists is staged by the runtime before
-    // it returns, so the temporary plan can go).  Otherwise: temporary device memory and a wait.
+    // and the library does not wait; the temporary plan, whose host image the copy of the lists
+    // reads, is freed by a host function queued on the stream behind the launches.  Otherwise:
+    // temporary device memory and a wait.
     const size_t ws_part = pv::align_up(plan->workspace_bytes, 256);
     const bool ws_ok = workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u) == 0;
     if (plan->workspace_bytes > 0 && (!ws_ok || workspace_bytes < plan->workspace_bytes)) {
@@ -396,8 +397,17 @@ pv_status pv_multi_token_paged_attn(const pv_pool_desc *pool, int32_t num_q_head
     if (s == PV_OK)
         s = pv_multi_token_paged_attn_planned(plan, q, k_pages, v_pages, page_table, scale, out,
                                               workspace, workspace_bytes, stream);
-    if (s == PV_OK && wait &&
-        hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess)
+    if (s == PV_OK && !wait) {
+        // the plan holds no device memory and no events here: freeing it is a plain delete,
+        // which a host function may do (it must not call into the runtime)
+        if (hipLaunchHostFunc(static_cast<hipStream_t>(stream),
+                              [](void *p) { delete static_cast<pv_plan *>(p); },
+                              plan) == hipSuccess)
+            return PV_OK;
+        wait = true;  // could not queue it: wait instead
+    }
+    if (s != PV_OK) wait = true;  // a copy that reads the plan's image may have been queued
+    if (wait && hipStreamSynchronize(static_cast<hipStream_t>(stream)) != hipSuccess && s == PV_OK)
         s = PV_ERR_HIP;
     pv_plan_destroy(plan);
     return s;

@@ -71,6 +71,41 @@ def test_one_shot_entry_points_match_planned(oracle):
     assert np.array_equal(planned, one)
 
 
+def test_one_shot_calls_back_to_back_and_without_room_for_the_lists(oracle, monkeypatch):
+    """The one-shot attention call keeps its temporary plan alive until the stream has passed the
+    launches (it is freed by a host function queued behind them): several calls in a row without
+    a wait in between, each into its own output, then once more with no workspace at all (the
+    lists then go to temporary device memory and the call waits).  All give the planned result."""
+    import torch
+    from paper_2312_05516_amd import binding as pv
+    monkeypatch.setenv("PV_SPLIT_TARGET", "1")  # no split KV ranges: no partial results to hold
+    b = wl.custom([300, 17, 900, 0], [33, 1, 140, 64], num_q_heads=8, num_kv_heads=2, head_dim=128,
+                  dtype="bf16", seed=47)
+    case = H.make_case(b)
+    planned, kpool, vpool = H.gpu_run(case)
+    desc = pv.pool_desc(b.num_pages, b.num_kv_heads, b.head_dim, b.dtype)
+    kp, vp = H.to_dev_bits(kpool.reshape(case.k_pool0.shape), b.dtype), \
+        H.to_dev_bits(vpool.reshape(case.v_pool0.shape), b.dtype)  # pools after the append
+    q = H.to_dev_bits(case.q, b.dtype)
+    table = torch.from_numpy(b.page_table).cuda()
+    nbytes = pv.attn_workspace_bytes(desc, b.num_q_heads, b.num_reqs, b.total_q, int(b.kv_lens.max()))
+    outs, spaces = [], []
+    for i in range(4):
+        outs.append(torch.full_like(q, float("nan")))
+        spaces.append(torch.empty(nbytes, dtype=torch.uint8, device="cuda"))
+    for i in range(4):
+        pv.multi_token_paged_attn(desc, b.num_q_heads, q, kp, vp, table, b.max_pages_per_req,
+                                  b.ctx_lens, b.q_lens, b.q_start, b.scale, outs[i], spaces[i])
+    torch.cuda.synchronize()
+    for o in outs:
+        assert np.array_equal(H.from_dev_bits(o), planned)
+    last = torch.full_like(q, float("nan"))
+    pv.multi_token_paged_attn(desc, b.num_q_heads, q, kp, vp, table, b.max_pages_per_req,
+                              b.ctx_lens, b.q_lens, b.q_start, b.scale, last, None)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.from_dev_bits(last), planned)
+
+
 def test_empty_batch_is_a_no_op():
     import torch
     from paper_2312_05516_amd import binding as pv
