@@ -131,7 +131,9 @@ void pv_plan_destroy(pv_plan *plan);
  * pv_plan_upload_to: the caller owns the memory.  Copies pv_plan_device_bytes(plan) bytes into
  * device_buf (256-byte aligned, at least that large, else PV_ERR_WORKSPACE) with one asynchronous
  * copy on `stream`, allocates nothing and does not wait; launches on the same stream may follow
- * at once.  The buffer must stay untouched until the last launch that uses the plan has finished.
+ * at once.  The buffer must stay untouched until the last launch that uses the plan has finished,
+ * and the plan (the copy reads its host memory) must not be destroyed before `stream` has passed
+ * the copy.
  *
  * pv_plan_upload: convenience.  Allocates device memory that the plan then owns (freed by
  * pv_plan_destroy), copies, and waits for the copy.  Idempotent.
@@ -223,7 +225,8 @@ pv_status pv_multi_token_paged_attn_planned(pv_plan *plan, const void *q, const 
  * to 256 + pv_plan_workspace_bytes > pv_static_scratch_bytes()): use the planned call then.
  * All calls on one GPU share that GPU's array: two calls whose execution may overlap (different
  * streams, or the same plan replayed while an earlier launch still runs) race on it.  Nothing in
- * the array needs clearing between calls.
+ * the array needs clearing between calls.  The plan must not be destroyed before `stream` has
+ * passed the call (the copy reads its host memory).
  */
 size_t pv_static_scratch_bytes(void);
 pv_status pv_multi_token_paged_attn_noalloc(pv_plan *plan, const void *q, const void *k_pages,
