@@ -140,3 +140,41 @@ def test_tile256_batch_of_medium_ranges_without_a_limit_set_by_hand(oracle, monk
     items, rest = _tile_items(b)
     assert len(items) == 2 * (2 + 2 + 3 + 2) and rest > 0
     check_case(oracle, H.make_case(b, fill="nan"))
+
+
+@pytest.mark.parametrize("idx", range(10))
+def test_tile256_random_batches(oracle, idx, monkeypatch):
+    """Seeded random batches with the length threshold of the 256-row kernel at its lowest, so
+    that every unit of at least 256 rows has tiles there: ranges of a few blocks up to a hundred,
+    cut and whole, causal boundaries at every offset inside a block, rests for the other kernels,
+    group sizes 1 to 16, both dtypes, small and large scales."""
+    monkeypatch.setenv("PV_TILE_MIN_KEYS", "1")
+    rng = np.random.default_rng(900 + idx)
+    group = int(rng.choice([1, 2, 4, 8, 16]))
+    hkv = int(rng.choice([1, 2]))
+    reqs = int(rng.integers(1, 5))
+    ctx = [int(rng.integers(0, 3200)) for _ in range(reqs)]
+    # at least one request with 256 rows or more, the others anything from a generation step up
+    qn = [int(rng.integers(1, max(2, 700 // group))) for _ in range(reqs)]
+    qn[0] = int(rng.integers((256 + group - 1) // group, (256 + group - 1) // group + 600 // group + 1))
+    if idx % 3 == 0:
+        monkeypatch.setenv("PV_SPLIT_TARGET", "4")  # whole ranges
+    b = wl.custom(ctx, qn, num_q_heads=group * hkv, num_kv_heads=hkv, head_dim=128,
+                  dtype="bf16" if idx % 2 else "f16", seed=910 + idx,
+                  value_std=0.5 if idx % 4 == 1 else 1.0)
+    items, _ = _tile_items(b)
+    assert items
+    print(f"random {idx}: G={group} Hkv={hkv} ctx={ctx} q={qn}: {len(items)} items of the 256-row "
+          f"kernel, ranges {min(int(i[5] - i[4]) for i in items)}..{max(int(i[5] - i[4]) for i in items)}",
+          flush=True)
+    scale = None if idx % 4 else 0.3  # every fourth: the instantiation that scales in fp32
+    case = H.make_case(b, fill="nan")
+    if scale is None:
+        check_case(oracle, case)
+    else:
+        got, _, _ = H.gpu_run(case, scale=scale)
+        from test_gpu_parity import oracle_out
+        want = oracle_out(oracle, case, scale=scale)
+        err = np.abs(H.bits_to_f64(got, b.dtype) - want).max()
+        print(f"  scale {scale}: max abs err {err:.3e}", flush=True)
+        assert err <= H.TOL[b.dtype]
